@@ -1,0 +1,139 @@
+/*
+ * rtlynx.h - C ABI of the MI355X (gfx950) RT-Lynx hot path:
+ *            online 2:4 activation sparsification + activation-sparse x dense-weight linear.
+ *
+ * Problem statement (paper, Preliminary: Eq. linear_layer / Eq. sparse_activation; Alg. 1):
+ *     Y = S(X) W^T ,  X in R^{M x K} (tokens x D_in),  W in R^{N x K} (D_out x D_in),
+ *     S(X) = s * TopK_{2:4}(X),  s = sqrt(|X|^2 / (|TopK(X)|^2 + eps)).
+ *
+ * General conventions
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller. The library never allocates,
+ *    frees or synchronises; all work is enqueued on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream) and the call returns immediately.
+ *  - bf16 tensors are row-major with the contraction dimension K contiguous; `ld*` are row
+ *    strides in ELEMENTS. Inputs are never modified; outputs are fully overwritten.
+ *  - All argument checks happen before any launch, so error paths touch no memory:
+ *      RTL_ERR_NULL       a required pointer is NULL
+ *      RTL_ERR_SHAPE      negative size, K not a multiple of the required granule, ld < extent
+ *      RTL_ERR_ALIGN      a pointer or a row stride breaks the stated alignment
+ *      RTL_ERR_WORKSPACE  workspace NULL or smaller than the matching *_workspace() query
+ *      RTL_ERR_ARG        an enum value out of range, or eps negative / not finite
+ *      RTL_ERR_HIP        the HIP runtime refused a launch (message via hipGetLastError)
+ *  - M == 0 or N == 0 is RTL_OK with no launch.
+ *  - Arithmetic: bf16 operands, fp32 accumulation, fp32 -> bf16 round-to-nearest-even on store.
+ */
+#ifndef RTLYNX_H
+#define RTLYNX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RTL_OK = 0,
+    RTL_ERR_NULL = 1,
+    RTL_ERR_SHAPE = 2,
+    RTL_ERR_ALIGN = 3,
+    RTL_ERR_WORKSPACE = 4,
+    RTL_ERR_ARG = 5,
+    RTL_ERR_HIP = 6
+} rtl_status;
+
+/* Scope of the two norms in the compensation factor s (method section, "Norm-Compensated
+ * Sparsification", and Alg. 1 step 4). The method section states it for one 1x4 group (GROUP,
+ * the default reading); Alg. 1 writes one scalar for the whole activation (TENSOR); ROW is the
+ * per-token reading in between. NONE is the naive "Sparse Activation" baseline of the paper. */
+typedef enum {
+    RTL_COMP_NONE = 0,
+    RTL_COMP_GROUP = 1,
+    RTL_COMP_ROW = 2,
+    RTL_COMP_TENSOR = 3
+} rtl_comp;
+
+/* ---------------------------------------------------------------------------------------------
+ * rtl_sparsify_pack - Alg. 1 steps "X~ <- TopK(X)" and "s, S(X) <- s X~", followed by the
+ * compression into the operand format of the paper's App. A (kept values + 2-bit positions).
+ *
+ *   X      [M, K] bf16, row stride ldx (>= K). 16-byte aligned base, ldx % 8 == 0, K % 8 == 0.
+ *   comp   scope of s (see rtl_comp); eps is the stabiliser inside the square root (paper: 1e-8).
+ *   vals   [M, K/2] bf16, dense rows (stride K/2), 16-byte aligned. For every aligned group of four
+ *          g = k/4 the two entries of largest magnitude, in ascending position order. Magnitude
+ *          is compared on the bf16 bit pattern without its sign bit; ties keep the lower index.
+ *          comp == GROUP: the stored values are bf16_rne(s_g * x) with
+ *              s_g = sqrtf((((x0^2+x1^2)+x2^2)+x3^2) / ((ka^2+kb^2)+eps))   (fp32, this order);
+ *          otherwise the stored values are the untouched inputs.
+ *   meta   [M, K/8] bytes, 4-byte aligned. Group g of a row sits in nibble (g & 1) of byte g/2;
+ *          nibble = pos0 | pos1 << 2 with pos0 < pos1 the kept positions inside the group.
+ *   scale  fp32 output, required for ROW ([M]) and TENSOR ([1]), ignored otherwise (may be NULL).
+ *          s is constant along the contraction for these scopes, so it is handed out for an fp32
+ *          multiplication of the GEMM result instead of being rounded into `vals`.
+ *   workspace  device scratch of rtl_sparsify_pack_workspace(M, K, comp) bytes (0 unless TENSOR),
+ *          256-byte aligned; contents are overwritten. May be NULL when the query returns 0.
+ * ------------------------------------------------------------------------------------------- */
+size_t rtl_sparsify_pack_workspace(int64_t M, int64_t K, rtl_comp comp);
+rtl_status rtl_sparsify_pack(const void* X, int64_t M, int64_t K, int64_t ldx,
+                             rtl_comp comp, float eps,
+                             void* vals, void* meta, float* scale,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * rtl_packed_linear - Alg. 1 step "Y_s <- S(X) W^T" on an already compressed activation
+ * (App. A: the 2-bit positions pick the matching rows of the dense operand), executed on the
+ * structured-sparse matrix instructions; optional "+ b" of Alg. 2.
+ *
+ *   vals, meta  as written by rtl_sparsify_pack for an [M, K] activation. K % 64 == 0.
+ *   row_scale   NULL, or fp32 [M]: Y[m, :] is multiplied by row_scale[m] in fp32 before the bias.
+ *   tensor_scale NULL, or fp32 [1]: Y is multiplied by tensor_scale[0] likewise.
+ *   W      [N, K] bf16, row stride ldw (>= K), 16-byte aligned base, ldw % 8 == 0.
+ *   bias   NULL or bf16 [N].
+ *   Y      [M, N] bf16, row stride ldy (>= N). 2-byte aligned is enough.
+ *   workspace  rtl_packed_linear_workspace(M, N, K) bytes, 256-byte aligned (partial tiles of the
+ *          split contraction; may be 0).
+ * ------------------------------------------------------------------------------------------- */
+size_t rtl_packed_linear_workspace(int64_t M, int64_t N, int64_t K);
+rtl_status rtl_packed_linear(const void* vals, const void* meta,
+                             const float* row_scale, const float* tensor_scale,
+                             const void* W, const void* bias, void* Y,
+                             int64_t M, int64_t N, int64_t K, int64_t ldw, int64_t ldy,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * rtl_sparse_linear - the whole of Alg. 1 without its LoRA branch:
+ *     Y = compensate(sparsify_2:4(X)) W^T (+ b).
+ * Equivalent to rtl_sparsify_pack into the workspace followed by rtl_packed_linear.
+ *
+ *   X [M,K] bf16 (ldx), W [N,K] bf16 (ldw), bias NULL or bf16 [N], Y [M,N] bf16 (ldy).
+ *   K % 64 == 0; X and W 16-byte aligned with ldx % 8 == 0 and ldw % 8 == 0.
+ *   workspace  rtl_sparse_linear_workspace(M, N, K, comp) bytes, 256-byte aligned.
+ * ------------------------------------------------------------------------------------------- */
+size_t rtl_sparse_linear_workspace(int64_t M, int64_t N, int64_t K, rtl_comp comp);
+rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, void* Y,
+                             int64_t M, int64_t N, int64_t K,
+                             int64_t ldx, int64_t ldw, int64_t ldy,
+                             rtl_comp comp, float eps,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * rtl_dense_linear - Eq. (linear_layer), Y = X W^T (+ b), on the dense matrix instructions.
+ * The denominator of every speedup the paper reports ("GEMM" column of its kernel tables).
+ * Same layouts and alignment rules as rtl_sparse_linear; K % 64 == 0.
+ *   workspace  rtl_dense_linear_workspace(M, N, K) bytes, 256-byte aligned (may be 0).
+ * ------------------------------------------------------------------------------------------- */
+size_t rtl_dense_linear_workspace(int64_t M, int64_t N, int64_t K);
+rtl_status rtl_dense_linear(const void* X, const void* W, const void* bias, void* Y,
+                            int64_t M, int64_t N, int64_t K,
+                            int64_t ldx, int64_t ldw, int64_t ldy,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* Human-readable name of a status code; never NULL. */
+const char* rtl_status_str(rtl_status s);
+/* Library version string, e.g. "rtlynx-gfx950 0.1". */
+const char* rtl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTLYNX_H */

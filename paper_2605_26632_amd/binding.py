@@ -1,0 +1,165 @@
+"""Thin ctypes binding of librtlynx.so: argument marshalling only.
+
+Same entry points as include/rtlynx.h. Tensors are torch CUDA tensors (used for device memory
+and the current stream); every step of the path runs inside the library's HIP kernels. There is
+no fallback: a missing library or a non-zero status raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librtlynx.so")
+
+COMP_NONE, COMP_GROUP, COMP_ROW, COMP_TENSOR = 0, 1, 2, 3
+COMP = {"none": COMP_NONE, "group": COMP_GROUP, "row": COMP_ROW, "tensor": COMP_TENSOR}
+
+SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linear_workspace",
+           "rtl_packed_linear", "rtl_sparse_linear_workspace", "rtl_sparse_linear",
+           "rtl_dense_linear_workspace", "rtl_dense_linear", "rtl_status_str", "rtl_version"]
+
+_lib = None
+
+
+class RtlError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s failed: %s" % (where, status_str(status)))
+
+
+def lib():
+    """Load librtlynx.so (built in-tree by paper_2605_26632_amd/build.py). Raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("librtlynx.so is not built: run `python -m paper_2605_26632_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        i64, vp, sz, fl, ci = C.c_int64, C.c_void_p, C.c_size_t, C.c_float, C.c_int
+        L.rtl_sparsify_pack_workspace.argtypes = [i64, i64, ci]
+        L.rtl_sparsify_pack_workspace.restype = sz
+        L.rtl_sparsify_pack.argtypes = [vp, i64, i64, i64, ci, fl, vp, vp, vp, vp, sz, vp]
+        L.rtl_sparsify_pack.restype = ci
+        L.rtl_packed_linear_workspace.argtypes = [i64, i64, i64]
+        L.rtl_packed_linear_workspace.restype = sz
+        L.rtl_packed_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, sz, vp]
+        L.rtl_packed_linear.restype = ci
+        L.rtl_sparse_linear_workspace.argtypes = [i64, i64, i64, ci]
+        L.rtl_sparse_linear_workspace.restype = sz
+        L.rtl_sparse_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, fl, vp, sz, vp]
+        L.rtl_sparse_linear.restype = ci
+        L.rtl_dense_linear_workspace.argtypes = [i64, i64, i64]
+        L.rtl_dense_linear_workspace.restype = sz
+        L.rtl_dense_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, sz, vp]
+        L.rtl_dense_linear.restype = ci
+        L.rtl_status_str.argtypes = [ci]
+        L.rtl_status_str.restype = C.c_char_p
+        L.rtl_version.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_str(status):
+    return lib().rtl_status_str(int(status)).decode()
+
+
+def version():
+    return lib().rtl_version().decode()
+
+
+def _p(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, where):
+    if status != 0:
+        raise RtlError(status, where)
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("librtlynx takes device tensors only")
+
+
+def _ws(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def sparsify_pack(X, comp=COMP_GROUP, eps=1e-8, out=None):
+    """rtl_sparsify_pack: X bf16 [M,K] -> (vals bf16 [M,K/2], meta u8 [M,K/8], scale fp32 or None)."""
+    _need_cuda(X)
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    dev = X.device
+    if out is None:
+        vals = torch.empty((M, K // 2), dtype=torch.bfloat16, device=dev)
+        meta = torch.empty((M, K // 8), dtype=torch.uint8, device=dev)
+    else:
+        vals, meta = out
+    scale = None
+    if comp == COMP_ROW:
+        scale = torch.empty((M,), dtype=torch.float32, device=dev)
+    elif comp == COMP_TENSOR:
+        scale = torch.empty((1,), dtype=torch.float32, device=dev)
+    L = lib()
+    nws = L.rtl_sparsify_pack_workspace(M, K, comp)
+    ws = _ws(nws, dev)
+    st = L.rtl_sparsify_pack(_p(X), M, K, X.stride(0), comp, eps, _p(vals), _p(meta), _p(scale),
+                             _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_sparsify_pack")
+    return vals, meta, scale
+
+
+def packed_linear(vals, meta, W, bias=None, row_scale=None, tensor_scale=None, out=None, ws=None):
+    """rtl_packed_linear: Y = decode(vals, meta) W^T (* scales) (+ bias), bf16 [M,N]."""
+    _need_cuda(vals, meta, W)
+    M, K = vals.shape[0], vals.shape[1] * 2
+    N = W.shape[0]
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=W.device) if out is None else out
+    L = lib()
+    if ws is None:
+        ws = _ws(L.rtl_packed_linear_workspace(M, N, K), W.device)
+    st = L.rtl_packed_linear(_p(vals), _p(meta), _p(row_scale), _p(tensor_scale), _p(W), _p(bias),
+                             _p(Y), M, N, K, W.stride(0), Y.stride(0), _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_packed_linear")
+    return Y
+
+
+def sparse_linear_workspace(M, N, K, comp=COMP_GROUP):
+    return int(lib().rtl_sparse_linear_workspace(M, N, K, comp))
+
+
+def sparse_linear(X, W, bias=None, comp=COMP_GROUP, eps=1e-8, out=None, ws=None):
+    """rtl_sparse_linear: Y = compensate(sparsify_2:4(X)) W^T (+ bias), bf16 [M,N]."""
+    _need_cuda(X, W)
+    M, K = X.shape
+    N = W.shape[0]
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if out is None else out
+    L = lib()
+    if ws is None:
+        ws = _ws(L.rtl_sparse_linear_workspace(M, N, K, comp), X.device)
+    st = L.rtl_sparse_linear(_p(X), _p(W), _p(bias), _p(Y), M, N, K, X.stride(0), W.stride(0),
+                             Y.stride(0), comp, eps, _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_sparse_linear")
+    return Y
+
+
+def dense_linear(X, W, bias=None, out=None, ws=None):
+    """rtl_dense_linear: Y = X W^T (+ bias), bf16 [M,N]."""
+    _need_cuda(X, W)
+    M, K = X.shape
+    N = W.shape[0]
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if out is None else out
+    L = lib()
+    if ws is None:
+        ws = _ws(L.rtl_dense_linear_workspace(M, N, K), X.device)
+    st = L.rtl_dense_linear(_p(X), _p(W), _p(bias), _p(Y), M, N, K, X.stride(0), W.stride(0),
+                            Y.stride(0), _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_dense_linear")
+    return Y

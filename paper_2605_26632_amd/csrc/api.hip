@@ -1,0 +1,181 @@
+// C ABI of librtlynx: argument validation and dispatch. Every check precedes any launch, so the
+// error paths can be exercised on a host without a GPU.
+#include <cmath>
+#include "rtl_internal.h"
+
+namespace {
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool comp_ok(rtl_comp c) { return c >= RTL_COMP_NONE && c <= RTL_COMP_TENSOR; }
+inline bool eps_ok(float e) { return std::isfinite(e) && e >= 0.0f; }
+
+// Layout of the rtl_sparse_linear workspace: [vals | meta | scale | pack scratch | gemm scratch]
+struct SparseWs {
+    size_t vals, meta, scale, pack, gemm, total;
+};
+SparseWs sparse_ws(int64_t M, int64_t N, int64_t K, rtl_comp comp) {
+    SparseWs w{};
+    size_t off = 0;
+    w.vals = off; off += round_up((size_t)M * (size_t)(K / 2) * 2, 256);
+    w.meta = off; off += round_up((size_t)M * (size_t)(K / 8), 256);
+    w.scale = off; off += round_up((size_t)(M > 0 ? M : 1) * sizeof(float), 256);
+    w.pack = off; off += round_up(rtl_sparsify_pack_workspace(M, K, comp), 256);
+    w.gemm = off; off += round_up(rtl::gemm_workspace_bytes(true, M, N, K), 256);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rtl_status_str(rtl_status s) {
+    switch (s) {
+        case RTL_OK: return "RTL_OK";
+        case RTL_ERR_NULL: return "RTL_ERR_NULL: a required pointer is NULL";
+        case RTL_ERR_SHAPE: return "RTL_ERR_SHAPE: bad size, K granule or leading dimension";
+        case RTL_ERR_ALIGN: return "RTL_ERR_ALIGN: pointer or stride alignment";
+        case RTL_ERR_WORKSPACE: return "RTL_ERR_WORKSPACE: workspace missing or too small";
+        case RTL_ERR_ARG: return "RTL_ERR_ARG: enum out of range or bad eps";
+        case RTL_ERR_HIP: return "RTL_ERR_HIP: HIP runtime error at launch";
+    }
+    return "RTL_ERR_UNKNOWN";
+}
+
+const char* rtl_version(void) { return "rtlynx-gfx950 0.1"; }
+
+size_t rtl_sparsify_pack_workspace(int64_t M, int64_t K, rtl_comp comp) {
+    (void)K;
+    if (comp != RTL_COMP_TENSOR || M <= 0) return 0;
+    return (size_t)M * 2 * sizeof(float);
+}
+
+rtl_status rtl_sparsify_pack(const void* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
+                             float eps, void* vals, void* meta, float* scale, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    if (M < 0 || K < 0 || K % 8 != 0 || ldx < K || K > (int64_t)1 << 30) return RTL_ERR_SHAPE;
+    if (M == 0 || K == 0) return RTL_OK;
+    if (!X || !vals || !meta) return RTL_ERR_NULL;
+    if ((comp == RTL_COMP_ROW || comp == RTL_COMP_TENSOR) && !scale) return RTL_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned(X, 16) || !aligned(vals, 16) || !aligned(meta, 4))
+        return RTL_ERR_ALIGN;
+    if (scale && !aligned(scale, 4)) return RTL_ERR_ALIGN;
+    const size_t need = rtl_sparsify_pack_workspace(M, K, comp);
+    if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    hipError_t e = rtl::launch_sparsify_pack(
+        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, static_cast<uint16_t*>(vals),
+        static_cast<uint8_t*>(meta), scale, static_cast<float*>(workspace),
+        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+static rtl_status check_linear(const void* A, const void* W, const void* Y, int64_t M, int64_t N,
+                               int64_t K, int64_t lda, int64_t ldw, int64_t ldy, int64_t a_extent) {
+    if (M < 0 || N < 0 || K <= 0 || K % 64 != 0 || lda < a_extent || ldw < K || ldy < N)
+        return RTL_ERR_SHAPE;
+    if (M > ((int64_t)1 << 30) || N > ((int64_t)1 << 30) || K > ((int64_t)1 << 30))
+        return RTL_ERR_SHAPE;
+    if (M == 0 || N == 0) return RTL_OK;
+    if (!A || !W || !Y) return RTL_ERR_NULL;
+    if (lda % 8 != 0 || ldw % 8 != 0 || !aligned(A, 16) || !aligned(W, 16) || !aligned(Y, 2))
+        return RTL_ERR_ALIGN;
+    return RTL_OK;
+}
+
+size_t rtl_packed_linear_workspace(int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return rtl::gemm_workspace_bytes(true, M, N, K);
+}
+
+rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* row_scale,
+                             const float* tensor_scale, const void* W, const void* bias, void* Y,
+                             int64_t M, int64_t N, int64_t K, int64_t ldw, int64_t ldy,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    rtl_status st = check_linear(vals, W, Y, M, N, K, K / 2, ldw, ldy, K / 2);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (!meta) return RTL_ERR_NULL;
+    if (!aligned(meta, 8) || (bias && !aligned(bias, 2))) return RTL_ERR_ALIGN;
+    const size_t need = rtl_packed_linear_workspace(M, N, K);
+    if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    rtl::GemmArgs g{};
+    g.A = static_cast<const uint16_t*>(vals);
+    g.meta = static_cast<const uint8_t*>(meta);
+    g.W = static_cast<const uint16_t*>(W);
+    g.bias = static_cast<const uint16_t*>(bias);
+    g.row_scale = row_scale;
+    g.tensor_scale = tensor_scale;
+    g.Y = static_cast<uint16_t*>(Y);
+    g.partials = static_cast<float*>(workspace);
+    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
+    hipError_t e = rtl::launch_gemm(true, g, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+size_t rtl_sparse_linear_workspace(int64_t M, int64_t N, int64_t K, rtl_comp comp) {
+    if (M <= 0 || N <= 0 || K <= 0 || !comp_ok(comp)) return 0;
+    return sparse_ws(M, N, K, comp).total;
+}
+
+rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, void* Y, int64_t M,
+                             int64_t N, int64_t K, int64_t ldx, int64_t ldw, int64_t ldy,
+                             rtl_comp comp, float eps, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    rtl_status st = check_linear(X, W, Y, M, N, K, ldx, ldw, ldy, K);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (bias && !aligned(bias, 2)) return RTL_ERR_ALIGN;
+    const SparseWs ws = sparse_ws(M, N, K, comp);
+    if (!workspace || workspace_bytes < ws.total) return RTL_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    float* scale = reinterpret_cast<float*>(base + ws.scale);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = rtl::launch_sparsify_pack(
+        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
+        reinterpret_cast<uint16_t*>(base + ws.vals), base + ws.meta, scale,
+        reinterpret_cast<float*>(base + ws.pack), s);
+    if (e != hipSuccess) return RTL_ERR_HIP;
+    rtl::GemmArgs g{};
+    g.A = reinterpret_cast<const uint16_t*>(base + ws.vals);
+    g.meta = base + ws.meta;
+    g.W = static_cast<const uint16_t*>(W);
+    g.bias = static_cast<const uint16_t*>(bias);
+    g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
+    g.tensor_scale = comp == RTL_COMP_TENSOR ? scale : nullptr;
+    g.Y = static_cast<uint16_t*>(Y);
+    g.partials = reinterpret_cast<float*>(base + ws.gemm);
+    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
+    e = rtl::launch_gemm(true, g, s);
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+size_t rtl_dense_linear_workspace(int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return rtl::gemm_workspace_bytes(false, M, N, K);
+}
+
+rtl_status rtl_dense_linear(const void* X, const void* W, const void* bias, void* Y, int64_t M,
+                            int64_t N, int64_t K, int64_t ldx, int64_t ldw, int64_t ldy,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    rtl_status st = check_linear(X, W, Y, M, N, K, ldx, ldw, ldy, K);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (bias && !aligned(bias, 2)) return RTL_ERR_ALIGN;
+    const size_t need = rtl_dense_linear_workspace(M, N, K);
+    if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    rtl::GemmArgs g{};
+    g.A = static_cast<const uint16_t*>(X);
+    g.W = static_cast<const uint16_t*>(W);
+    g.bias = static_cast<const uint16_t*>(bias);
+    g.Y = static_cast<uint16_t*>(Y);
+    g.partials = static_cast<float*>(workspace);
+    g.M = M; g.N = N; g.K = K; g.lda = ldx; g.ldw = ldw; g.ldy = ldy;
+    hipError_t e = rtl::launch_gemm(false, g, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before touching any memory."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_26632_amd import binding as rtl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "rtlynx.h")).read()
+    declared = set(re.findall(r"\b(rtl_[a-z_]+)\s*\(", hdr))
+    assert declared == set(rtl.SYMBOLS), declared ^ set(rtl.SYMBOLS)
+    L = rtl.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert rtl.version().startswith("rtlynx-gfx950")
+
+
+def test_status_strings():
+    for s in range(7):
+        assert rtl.status_str(s).startswith("RTL_")
+
+
+FAKE = 0x10000  # non-null, 256-byte aligned, never dereferenced: validation precedes any launch
+
+
+def test_sparsify_pack_rejects_bad_arguments():
+    L = rtl.lib()
+    f = L.rtl_sparsify_pack
+    ok_args = dict(X=FAKE, M=4, K=64, ldx=64, comp=1, eps=1e-8, vals=FAKE, meta=FAKE, scale=None,
+                   ws=None, wsb=0, stream=None)
+
+    def call(**kw):
+        a = dict(ok_args, **kw)
+        return f(a["X"], a["M"], a["K"], a["ldx"], a["comp"], a["eps"], a["vals"], a["meta"],
+                 a["scale"], a["ws"], a["wsb"], a["stream"])
+
+    assert call(K=12) == 2 and call(K=60) == 2          # K % 8
+    assert call(ldx=32) == 2 and call(M=-1) == 2
+    assert call(X=None) == 1 and call(vals=None) == 1 and call(meta=None) == 1
+    assert call(comp=2) == 1 and call(comp=3) == 1       # ROW / TENSOR need `scale`
+    assert call(X=FAKE + 2) == 3 and call(ldx=68) == 3
+    assert call(comp=7) == 5 and call(eps=-1.0) == 5 and call(eps=float("nan")) == 5
+    assert call(comp=3, scale=FAKE) == 4                 # TENSOR needs workspace
+    assert call(comp=3, scale=FAKE, ws=FAKE, wsb=8) == 4
+    assert call(M=0) == 0                                # empty input: OK, nothing launched
+    assert L.rtl_sparsify_pack_workspace(100, 64, 3) == 800
+    assert L.rtl_sparsify_pack_workspace(100, 64, 1) == 0
+
+
+def test_linear_entry_points_reject_bad_arguments():
+    L = rtl.lib()
+
+    def dense(X=FAKE, W=FAKE, bias=None, Y=FAKE, M=4, N=4, K=64, ldx=64, ldw=64, ldy=4, ws=FAKE, wsb=1 << 30):
+        return L.rtl_dense_linear(X, W, bias, Y, M, N, K, ldx, ldw, ldy, ws, wsb, None)
+
+    def sparse(X=FAKE, W=FAKE, bias=None, Y=FAKE, M=4, N=4, K=64, ldx=64, ldw=64, ldy=4, comp=1,
+               eps=1e-8, ws=FAKE, wsb=1 << 30):
+        return L.rtl_sparse_linear(X, W, bias, Y, M, N, K, ldx, ldw, ldy, comp, eps, ws, wsb, None)
+
+    for f in (dense, sparse):
+        assert f(K=32) == 2 and f(K=0) == 2 and f(ldy=2) == 2 and f(ldw=32) == 2 and f(N=-3) == 2
+        assert f(X=None) == 1 and f(W=None) == 1 and f(Y=None) == 1
+        assert f(W=FAKE + 8) == 3 and f(ldx=68) == 3 and f(Y=FAKE + 1) == 3
+        assert f(M=0) == 0 and f(N=0) == 0
+    assert sparse(comp=9) == 5 and sparse(eps=float("inf")) == 5
+    assert sparse(ws=None) == 4 and sparse(wsb=16) == 4 and sparse(ws=FAKE + 64) == 3
+    need = L.rtl_sparse_linear_workspace(4096, 3072, 12288, 1)
+    assert need >= 4096 * 12288 + 4096 * 12288 // 8
+
+    def packed(vals=FAKE, meta=FAKE, W=FAKE, Y=FAKE, M=4, N=4, K=64, ldw=64, ldy=4):
+        return L.rtl_packed_linear(vals, meta, None, None, W, None, Y, M, N, K, ldw, ldy, FAKE, 1 << 30, None)
+
+    assert packed(meta=None) == 1 and packed(vals=None) == 1 and packed(K=96) == 2
+    assert packed(meta=FAKE + 4) == 3 and packed(M=0) == 0
