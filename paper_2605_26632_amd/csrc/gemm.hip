@@ -4,10 +4,15 @@
 //   sparse: Y = S(X) W^T, S(X) compressed   (Alg. 1 "Y_s <- S(X) W^T", operand format of App. A;
 //                                            v_smfmac_f32_32x32x32_bf16)
 //
-// Both share one LDS-staged, double-buffered tile loop. A workgroup owns a BM x BN tile of Y and
-// walks K in steps of 64. The compressed activation is the FIRST matrix operand of SMFMAC (the
-// one that carries 2-of-4 structure along K), so tokens map to the instruction's rows and the
-// weight rows (K contiguous) map to its columns: no transposition of either tensor is needed.
+// Both share one tile loop. A workgroup owns a BM x BN tile of Y and walks K in stages; a stage is
+// two matrix-instruction sub-steps deep (64 dense k for the sparse kernel, 32 for the dense one, so
+// both spend the same number of matrix cycles per stage). Stages travel HBM/L2 -> LDS with
+// direct-to-LDS loads (no register staging) through a ring of LDS buffers, and each wave keeps the
+// operand fragments of the next sub-step in flight while the matrix core works on the current one.
+//
+// The compressed activation is the FIRST matrix operand of SMFMAC (the one that carries 2-of-4
+// structure along K), so tokens map to the instruction's rows and the weight rows (K contiguous)
+// map to its columns: no transposition of either tensor is needed.
 //
 // Operand layout of v_smfmac_f32_32x32x32_bf16 (measured on the device with one-hot operands):
 //   lane l: i = l % 32, kb = l / 32
@@ -16,8 +21,10 @@
 //                 pos0 | pos1 << 2 of the lane's g-th group
 //   B (16 bf16) : column i; element u < 8 is dense k = 8 kb + u, u >= 8 is k = 16 + 8 kb + (u - 8)
 //   D (16 fp32) : column i, register r is row 8 (r / 4) + 4 kb + r % 4
-// The labelling of k inside a 64-wide step is free as long as both operands agree; it is chosen
-// so that a lane reads 16-byte chunks from LDS and one 32-bit word of metadata per step.
+// v_mfma_f32_32x32x16_bf16: A and B (8 bf16) hold k = 8 kb + v of row / column i; D as above.
+// The labelling of k inside a stage is free as long as both operands agree; it is chosen so that
+// a lane reads whole 16-byte chunks from LDS and one 32-bit word of metadata per stage.
+#include <type_traits>
 #include "rtl_internal.h"
 
 namespace rtl {
@@ -26,8 +33,6 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-constexpr int BK = 64;  // dense k per main-loop step
 
 union Frag8 {
     uint4 u;
@@ -45,22 +50,54 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? nan : r;
 }
 
-template <bool SPARSE, int BM, int BN>
+// Direct-to-LDS load of one wave: lane l fetches `bytes` (16 or 4) from its own global address and
+// the hardware writes them to LDS address lds_base + l * bytes (lds_base is wave-uniform and
+// travels in M0). Written as inline assembly so that the outstanding-load counter stays under
+// the kernel's own control: the loads of a stage are awaited with an explicit vmcnt wait right
+// before the barrier that publishes the stage, and reads of older stages never wait for them.
+__device__ __forceinline__ void lds_dma16(const void* gaddr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_base), "v"(gaddr) : "memory");
+}
+__device__ __forceinline__ void lds_dma4(const void* gaddr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                 :: "s"(lds_base), "v"(gaddr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_lgkm0() {   // vmcnt <= N, all LDS reads returned
+    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 0xF) | ((N >> 4) << 14));
+}
+
+// Per-stage LDS footprint. Rows of the A tile hold 64 bytes in both kernels (32 kept bf16 of 64
+// dense k, or 32 dense k); rows of the B tile hold 128 bytes (sparse) or 64 bytes (dense).
+template <bool SPARSE, int BM, int BN, int STAGES>
 struct Smem {
-    static constexpr int kABytes = SPARSE ? BM * 64 : BM * 128;
+    static constexpr int kABytes = BM * 64;
     static constexpr int kMetaBytes = SPARSE ? BM * 8 : 0;
-    static constexpr int kBBytes = BN * 128;
+    static constexpr int kBBytes = SPARSE ? BN * 128 : BN * 64;
     static constexpr int kStage = kABytes + kMetaBytes + kBBytes;
-    static constexpr int kTotal = 2 * kStage;
+    static constexpr int kTotal = STAGES * kStage;
 };
 
-// Byte offset of 16-byte chunk c of a row inside a tile whose rows hold 8 chunks (128 bytes).
+// 16-byte chunk c of a row, for tiles whose rows hold 8 chunks (128 bytes): XOR swizzle so that
+// the 8 rows a quarter-wave reads together fall into 8 different bank groups.
 __device__ __forceinline__ int swz8(int row, int c) { return row * 128 + ((c ^ (row & 7)) << 4); }
-// Same for rows of 4 chunks (64 bytes, the compressed activation): two rows share a 128-byte line.
+// Same for rows of 4 chunks (64 bytes): two rows share a 128-byte line.
 __device__ __forceinline__ int swz4(int row, int c) {
     const int q = row * 4 + c;
     const int line = q >> 3;
     return (line * 8 + ((q & 7) ^ (line & 7))) << 4;
+}
+// Inverse maps: which (row, c) lives at chunk position p of the tile.
+__device__ __forceinline__ void unswz8(int p, int& row, int& c) {
+    row = p >> 3;
+    c = (p & 7) ^ (row & 7);
+}
+__device__ __forceinline__ void unswz4(int p, int& row, int& c) {
+    const int line = p >> 3;
+    const int q = line * 8 + ((p & 7) ^ (line & 7));
+    row = q >> 2;
+    c = q & 3;
 }
 
 // Tile order: consecutive workgroup ids land on different XCDs (round robin), so ids are first
@@ -80,89 +117,74 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     pn = (t % per_group) / gsize;
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
-    constexpr int NT = WAVES_M * WAVES_N * 64;
+    constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
-    using L = Smem<SPARSE, BM, BN>;
-    constexpr int A_CHUNKS = SPARSE ? BM * 4 : BM * 8;
-    constexpr int B_CHUNKS = BN * 8;
-    static_assert(A_CHUNKS % NT == 0 && B_CHUNKS % NT == 0, "tile loads must divide evenly");
-    constexpr int A_PER_T = A_CHUNKS / NT, B_PER_T = B_CHUNKS / NT;
-    constexpr int A_CPR = SPARSE ? 4 : 8;          // 16-byte chunks per row per step
-    constexpr int A_STEP = SPARSE ? 32 : 64;       // elements of A consumed per step
+    using L = Smem<SPARSE, BM, BN, STAGES>;
+    constexpr int KSTAGE = SPARSE ? 64 : 32;          // dense k per stage
+    constexpr int A_ELEMS = 32;                       // bf16 of an A row per stage (both kernels)
+    // one wave-wide direct-to-LDS load moves 64 chunks of 16 bytes = 1 KiB
+    constexpr int A_LOADS = L::kABytes / 1024, B_LOADS = L::kBBytes / 1024;
+    static_assert(A_LOADS % NW == 0 && B_LOADS % NW == 0, "tile loads must divide over the waves");
+    constexpr int A_PER_W = A_LOADS / NW, B_PER_W = B_LOADS / NW;
+    constexpr int M_LOADS = SPARSE ? (BM * 8) / 256 : 0;  // metadata: 4 bytes per lane per load
+    static_assert(!SPARSE || M_LOADS == NW, "one metadata load per wave");
 
     extern __shared__ __align__(16) uint8_t smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lives in an SGPR
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     int pm, pn;
     tile_coords(blockIdx.x, tiles_m, tiles_n, pm, pn);
     const int64_t m0 = (int64_t)pm * BM, n0 = (int64_t)pn * BN;
-    const int KT = (int)(a.K / BK);
+    const int KT = (int)(a.K / KSTAGE);
 
-    // ---- global -> register staging (one 16-byte chunk per slot) ---------------------------
-    const uint16_t* pa[A_PER_T];
-    bool va[A_PER_T];
-    int la[A_PER_T];
+    // ---- global -> LDS: every lane owns fixed chunks; rows past the edge are clamped to the last
+    //      valid row (their products only reach outputs that are never stored) -----------------
+    const uint16_t* pa[A_PER_W];
 #pragma unroll
-    for (int s = 0; s < A_PER_T; ++s) {
-        const int id = tid + s * NT;
-        const int row = id / A_CPR, c = id % A_CPR;
-        va[s] = (m0 + row) < a.M;
-        pa[s] = a.A + (va[s] ? (m0 + row) : 0) * a.lda + c * 8;
-        la[s] = SPARSE ? swz4(row, c) : swz8(row, c);
+    for (int s = 0; s < A_PER_W; ++s) {
+        const int p = (wave * A_PER_W + s) * 64 + lane;
+        int row, c;
+        unswz4(p, row, c);
+        const int64_t gr = min(m0 + row, a.M - 1);
+        pa[s] = a.A + gr * a.lda + c * 8;
     }
-    const uint16_t* pb[B_PER_T];
-    bool vb[B_PER_T];
-    int lb[B_PER_T];
+    const uint16_t* pb[B_PER_W];
 #pragma unroll
-    for (int s = 0; s < B_PER_T; ++s) {
-        const int id = tid + s * NT;
-        const int row = id / 8, c = id % 8;
-        vb[s] = (n0 + row) < a.N;
-        pb[s] = a.W + (vb[s] ? (n0 + row) : 0) * a.ldw + c * 8;
-        lb[s] = L::kABytes + L::kMetaBytes + swz8(row, c);
+    for (int s = 0; s < B_PER_W; ++s) {
+        const int p = (wave * B_PER_W + s) * 64 + lane;
+        int row, c;
+        if constexpr (SPARSE) unswz8(p, row, c); else unswz4(p, row, c);
+        const int64_t gr = min(n0 + row, a.N - 1);
+        pb[s] = a.W + gr * a.ldw + c * 8;
     }
     const uint8_t* pmeta = nullptr;
-    bool vmeta = false;
     if constexpr (SPARSE) {
-        vmeta = tid < BM && (m0 + tid) < a.M;
-        pmeta = a.meta + (vmeta ? (m0 + tid) : 0) * (a.K / 8);
+        // wave w covers rows [32 w, 32 w + 32): lane -> row 32 w + lane / 2, half lane % 2
+        const int row = wave * 32 + (lane >> 1);
+        const int64_t gr = min(m0 + row, a.M - 1);
+        pmeta = a.meta + gr * (a.K / 8) + (lane & 1) * 4;
     }
 
-    uint4 ra[A_PER_T], rb[B_PER_T];
-    uint2 rmeta = make_uint2(0, 0);
-
-    auto gload = [&](int kt) {
+    auto gload = [&](int kt, int stage) {
+        const uint32_t base = lds0 + stage * L::kStage;
 #pragma unroll
-        for (int s = 0; s < A_PER_T; ++s) {
-            ra[s] = make_uint4(0, 0, 0, 0);
-            if (va[s]) ra[s] = *reinterpret_cast<const uint4*>(pa[s] + (int64_t)kt * A_STEP);
-        }
+        for (int s = 0; s < A_PER_W; ++s)
+            lds_dma16(pa[s] + (int64_t)kt * A_ELEMS, base + (wave * A_PER_W + s) * 1024);
 #pragma unroll
-        for (int s = 0; s < B_PER_T; ++s) {
-            rb[s] = make_uint4(0, 0, 0, 0);
-            if (vb[s]) rb[s] = *reinterpret_cast<const uint4*>(pb[s] + (int64_t)kt * BK);
-        }
-        if constexpr (SPARSE) {
-            rmeta = make_uint2(0, 0);
-            if (vmeta) rmeta = *reinterpret_cast<const uint2*>(pmeta + (int64_t)kt * 8);
-        }
+        for (int s = 0; s < B_PER_W; ++s)
+            lds_dma16(pb[s] + (int64_t)kt * KSTAGE,
+                      base + L::kABytes + L::kMetaBytes + (wave * B_PER_W + s) * 1024);
+        if constexpr (SPARSE) lds_dma4(pmeta + (int64_t)kt * 8, base + L::kABytes + wave * 256);
     };
-    auto lstore = [&](int stage) {
-        uint8_t* base = smem + stage * L::kStage;
-#pragma unroll
-        for (int s = 0; s < A_PER_T; ++s) *reinterpret_cast<uint4*>(base + la[s]) = ra[s];
-#pragma unroll
-        for (int s = 0; s < B_PER_T; ++s) *reinterpret_cast<uint4*>(base + lb[s]) = rb[s];
-        if constexpr (SPARSE) {
-            if (tid < BM) *reinterpret_cast<uint2*>(base + L::kABytes + tid * 8) = rmeta;
-        }
-    };
+    constexpr int LOADS_PER_STAGE = A_PER_W + B_PER_W + (SPARSE ? 1 : 0);
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 acc[TM][TN];
@@ -174,70 +196,106 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int li = lane & 31, kb = lane >> 5;
-    const int arow0 = wm * WTM + li;   // + tm * 32
-    const int brow0 = wn * WTN + li;   // + tn * 32
+    const int arow0 = wm * WTM + li;   // + i * 32
+    const int brow0 = wn * WTN + li;   // + j * 32
 
-    auto compute = [&](int stage) {
+    // operand fragments of one sub-step
+    struct Frags {
+        Frag8 a[TM];
+        Frag16 b[TN];   // dense kernel uses b[j].u[0] only
+    };
+    int ix_cur[TM], ix_nxt[TM];   // metadata words of the current / next stage (sparse only)
+
+    auto read_frags = [&](int stage, int sub, Frags& f) {
         const uint8_t* base = smem + stage * L::kStage;
         const uint8_t* bB = base + L::kABytes + L::kMetaBytes;
-        if constexpr (SPARSE) {
-            const uint8_t* bM = base + L::kABytes;
-            int idx[TM];
-            Frag8 fa[TM][2];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row = arow0 + i * 32;
-                idx[i] = *reinterpret_cast<const int*>(bM + row * 8 + kb * 4);
-                fa[i][0].u = *reinterpret_cast<const uint4*>(base + swz4(row, 2 * kb));
-                fa[i][1].u = *reinterpret_cast<const uint4*>(base + swz4(row, 2 * kb + 1));
-            }
+        for (int i = 0; i < TM; ++i)
+            f.a[i].u = *reinterpret_cast<const uint4*>(base + swz4(arow0 + i * 32, 2 * (SPARSE ? kb : sub) + (SPARSE ? sub : kb)));
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int row = brow0 + j * 32;
-                Frag16 f0, f1;
-                f0.u[0] = *reinterpret_cast<const uint4*>(bB + swz8(row, kb));
-                f0.u[1] = *reinterpret_cast<const uint4*>(bB + swz8(row, 4 + kb));
-                f1.u[0] = *reinterpret_cast<const uint4*>(bB + swz8(row, 2 + kb));
-                f1.u[1] = *reinterpret_cast<const uint4*>(bB + swz8(row, 6 + kb));
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa[i][0].v, f0.v, acc[i][j],
-                                                                          idx[i], 0, 0);
-                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(fa[i][1].v, f1.v, acc[i][j],
-                                                                          idx[i], 0, 1);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                Frag8 fa[TM], fb[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    fa[i].u = *reinterpret_cast<const uint4*>(base + swz8(arow0 + i * 32, 4 * kb + s));
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[j].u = *reinterpret_cast<const uint4*>(bB + swz8(brow0 + j * 32, 4 * kb + s));
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j],
-                                                                            0, 0, 0);
+        for (int j = 0; j < TN; ++j) {
+            const int row = brow0 + j * 32;
+            if constexpr (SPARSE) {
+                f.b[j].u[0] = *reinterpret_cast<const uint4*>(bB + swz8(row, 2 * sub + kb));
+                f.b[j].u[1] = *reinterpret_cast<const uint4*>(bB + swz8(row, 4 + 2 * sub + kb));
+            } else {
+                f.b[j].u[0] = *reinterpret_cast<const uint4*>(bB + swz4(row, 2 * sub + kb));
             }
         }
     };
+    auto read_idx = [&](int stage, int (&ix)[TM]) {
+        if constexpr (SPARSE) {
+            const uint8_t* bM = smem + stage * L::kStage + L::kABytes;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                ix[i] = *reinterpret_cast<const int*>(bM + (arow0 + i * 32) * 8 + kb * 4);
+        }
+    };
+    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag) {
+        constexpr int SUB = decltype(sub_tag)::value;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (SPARSE)
+                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[i].v, f.b[j].v, acc[i][j],
+                                                                          ix[i], 0, SUB);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i].v, bf16x8(f.b[j].v.lo),
+                                                                        acc[i][j], 0, 0, 0);
+            }
+    };
 
-    // ---- main loop: LDS double buffer, next tile in flight in registers ----------------------
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) gload(kt + 1);
-        compute(cur);
-        if (kt + 1 < KT) lstore(cur ^ 1);
-        __syncthreads();
-    }
+    // ---- prologue: STAGES-1 stages in flight, first one visible ------------------------------
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < KT) gload(s, s);
+    // wait for stage 0 only: the later STAGES-2 stages may stay in flight
+    if (KT >= STAGES - 1) wait_vmcnt_lgkm0<(STAGES - 2) * LOADS_PER_STAGE>();
+    else wait_vmcnt_lgkm0<0>();
+    __builtin_amdgcn_s_barrier();
+
+    Frags f0, f1;
+    read_frags(0, 0, f0);
+    read_idx(0, ix_cur);
+    wait_vmcnt_lgkm0<63>();            // fragments of sub-step 0 are in registers
+
+    // One stage of the main loop. HAS_LOAD: a stage STAGES-1 ahead exists and is requested now;
+    // HAS_NEXT: stage kt+1 exists and its first fragments are fetched behind the barrier.
+    int cur = 0;                       // LDS buffer of stage kt
+    auto stage_step = [&](int kt, auto has_load, auto has_next) {
+        constexpr bool HAS_LOAD = decltype(has_load)::value, HAS_NEXT = decltype(has_next)::value;
+        const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+        const int pre = cur == 0 ? STAGES - 1 : cur - 1;   // buffer of stage kt + STAGES - 1
+        // fragments of sub-step 1 and the stage STAGES-1 ahead start moving, then sub-step 0 runs
+        read_frags(cur, 1, f1);
+        if constexpr (HAS_LOAD) gload(kt + STAGES - 1, pre);
+        __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the matrix work
+        mma(f0, ix_cur, std::integral_constant<int, 0>{});
+        __builtin_amdgcn_sched_barrier(0);
+        // stage kt+1 must have landed, and this wave's reads of stage kt must be done, before the
+        // barrier lets anyone read stage kt+1 or overwrite stage kt
+        if constexpr (HAS_LOAD) wait_vmcnt_lgkm0<(STAGES - 2) * LOADS_PER_STAGE>();
+        else wait_vmcnt_lgkm0<0>();
+        __builtin_amdgcn_s_barrier();
+        if constexpr (HAS_NEXT) {
+            read_frags(nxt, 0, f0);
+            read_idx(nxt, ix_nxt);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mma(f1, ix_cur, std::integral_constant<int, 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (SPARSE && HAS_NEXT) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) ix_cur[i] = ix_nxt[i];
+        }
+        cur = nxt;
+    };
+    const int n_main = KT - (STAGES - 1);
+    int kt = 0;
+    for (; kt < n_main; ++kt) stage_step(kt, std::true_type{}, std::true_type{});
+    for (; kt < KT - 1; ++kt) stage_step(kt, std::false_type{}, std::true_type{});
+    stage_step(kt, std::false_type{}, std::false_type{});
 
     // ---- epilogue: optional fp32 scales, bias, bf16 RNE store -------------------------------
     const float ts = a.tensor_scale ? a.tensor_scale[0] : 1.0f;
@@ -262,10 +320,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     }
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N>
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
-    using L = Smem<SPARSE, BM, BN>;
-    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N>;
+    using L = Smem<SPARSE, BM, BN, STAGES>;
+    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES>;
     static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -283,8 +341,8 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
 size_t gemm_workspace_bytes(bool, int64_t, int64_t, int64_t) { return 0; }
 
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
-    if (sparse) return launch_cfg<true, 256, 256, 2, 4>(a, stream);
-    return launch_cfg<false, 256, 256, 2, 4>(a, stream);
+    if (sparse) return launch_cfg<true, 256, 256, 2, 4, 3>(a, stream);
+    return launch_cfg<false, 256, 256, 2, 4, 3>(a, stream);
 }
 
 }  // namespace rtl
