@@ -10,7 +10,8 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool comp_ok(rtl_comp c) { return c >= RTL_COMP_NONE && c <= RTL_COMP_TENSOR; }
 inline bool eps_ok(float e) { return std::isfinite(e) && e >= 0.0f; }
 
-// Layout of the rtl_sparse_linear workspace: [vals | meta | scale | pack scratch | gemm scratch]
+// Layout of the rtl_sparse_linear workspace:
+// [vals | k-major meta | scale | pack scratch | gemm scratch]
 struct SparseWs {
     size_t vals, meta, scale, pack, gemm, total;
 };
@@ -18,7 +19,7 @@ SparseWs sparse_ws(int64_t M, int64_t N, int64_t K, rtl_comp comp) {
     SparseWs w{};
     size_t off = 0;
     w.vals = off; off += round_up((size_t)M * (size_t)(K / 2) * 2, 256);
-    w.meta = off; off += round_up((size_t)M * (size_t)(K / 8), 256);
+    w.meta = off; off += round_up(rtl::kmajor_bytes(M, K), 256);
     w.scale = off; off += round_up((size_t)(M > 0 ? M : 1) * sizeof(float), 256);
     w.pack = off; off += round_up(rtl_sparsify_pack_workspace(M, K, comp), 256);
     w.gemm = off; off += round_up(rtl::gemm_workspace_bytes(true, M, N, K), 256);
@@ -67,7 +68,7 @@ rtl_status rtl_sparsify_pack(const void* X, int64_t M, int64_t K, int64_t ldx, r
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
     hipError_t e = rtl::launch_sparsify_pack(
         static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, static_cast<uint16_t*>(vals),
-        static_cast<uint8_t*>(meta), scale, static_cast<float*>(workspace),
+        static_cast<uint8_t*>(meta), nullptr, scale, static_cast<float*>(workspace),
         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
@@ -85,9 +86,10 @@ static rtl_status check_linear(const void* A, const void* W, const void* Y, int6
     return RTL_OK;
 }
 
+// rtl_packed_linear workspace: [k-major copy of the metadata | gemm scratch]
 size_t rtl_packed_linear_workspace(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    return rtl::gemm_workspace_bytes(true, M, N, K);
+    return round_up(rtl::kmajor_bytes(M, K), 256) + rtl::gemm_workspace_bytes(true, M, N, K);
 }
 
 rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* row_scale,
@@ -103,15 +105,19 @@ rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* ro
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
     rtl::GemmArgs g{};
     g.A = static_cast<const uint16_t*>(vals);
-    g.meta = static_cast<const uint8_t*>(meta);
+    uint8_t* km = static_cast<uint8_t*>(workspace);
+    hipError_t e = rtl::launch_meta_to_kmajor(static_cast<const uint8_t*>(meta), M, K, km,
+                                              static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return RTL_ERR_HIP;
+    g.meta = km;
     g.W = static_cast<const uint16_t*>(W);
     g.bias = static_cast<const uint16_t*>(bias);
     g.row_scale = row_scale;
     g.tensor_scale = tensor_scale;
     g.Y = static_cast<uint16_t*>(Y);
-    g.partials = static_cast<float*>(workspace);
+    g.partials = reinterpret_cast<float*>(km + round_up(rtl::kmajor_bytes(M, K), 256));
     g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
-    hipError_t e = rtl::launch_gemm(true, g, static_cast<hipStream_t>(stream));
+    e = rtl::launch_gemm(true, g, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
 
@@ -136,7 +142,7 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = rtl::launch_sparsify_pack(
         static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
-        reinterpret_cast<uint16_t*>(base + ws.vals), base + ws.meta, scale,
+        reinterpret_cast<uint16_t*>(base + ws.vals), nullptr, base + ws.meta, scale,
         reinterpret_cast<float*>(base + ws.pack), s);
     if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};

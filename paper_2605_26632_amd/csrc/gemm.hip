@@ -79,25 +79,22 @@ struct Smem {
     static constexpr int kTotal = STAGES * kStage;
 };
 
-// 16-byte chunk c of a row, for tiles whose rows hold 8 chunks (128 bytes): XOR swizzle so that
-// the 8 rows a quarter-wave reads together fall into 8 different bank groups.
-__device__ __forceinline__ int swz8(int row, int c) { return row * 128 + ((c ^ (row & 7)) << 4); }
-// Same for rows of 4 chunks (64 bytes): two rows share a 128-byte line.
-__device__ __forceinline__ int swz4(int row, int c) {
-    const int q = row * 4 + c;
-    const int line = q >> 3;
-    return (line * 8 + ((q & 7) ^ (line & 7))) << 4;
-}
+// LDS swizzles. A 16-byte read of a wave is served 16 lanes at a time over 64 four-byte banks, so
+// the 16 consecutive tile rows those lanes address (same logical chunk c) must land in 16 different
+// 16-byte slots modulo 256 bytes.
+// Rows of 8 chunks (128 bytes): two rows per 256 bytes; the row parity picks the half, c is XORed
+// with bits 1..3 of the row.
+__device__ __forceinline__ int swz8(int row, int c) { return row * 128 + ((c ^ ((row >> 1) & 7)) << 4); }
+// Rows of 4 chunks (64 bytes): four rows per 256 bytes; c is XORed with bits 2..3 of the row.
+__device__ __forceinline__ int swz4(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
 // Inverse maps: which (row, c) lives at chunk position p of the tile.
 __device__ __forceinline__ void unswz8(int p, int& row, int& c) {
     row = p >> 3;
-    c = (p & 7) ^ (row & 7);
+    c = (p & 7) ^ ((row >> 1) & 7);
 }
 __device__ __forceinline__ void unswz4(int p, int& row, int& c) {
-    const int line = p >> 3;
-    const int q = line * 8 + ((p & 7) ^ (line & 7));
-    row = q >> 2;
-    c = q & 3;
+    row = p >> 2;
+    c = (p & 3) ^ ((row >> 2) & 3);
 }
 
 // Tile order: consecutive workgroup ids land on different XCDs (round robin), so ids are first
@@ -167,24 +164,41 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     }
     const uint8_t* pmeta = nullptr;
     if constexpr (SPARSE) {
-        // wave w covers rows [32 w, 32 w + 32): lane -> row 32 w + lane / 2, half lane % 2
-        const int row = wave * 32 + (lane >> 1);
-        const int64_t gr = min(m0 + row, a.M - 1);
-        pmeta = a.meta + gr * (a.K / 8) + (lane & 1) * 4;
+        // k-major records: the 256 rows of this tile are one contiguous 2 KiB run per stage and
+        // wave w moves its 256-byte share (rows 32 w .. 32 w + 31), 4 bytes per lane
+        pmeta = a.meta + (m0 + wave * 32) * 8 + lane * 4;
     }
 
-    auto gload = [&](int kt, int stage) {
+    const int64_t meta_stride = ((a.M + 255) / 256 * 256) * 8;   // bytes between 64-k blocks
+    // Load number n (0 .. LOADS_PER_STAGE-1) of this wave for stage kt into ring buffer `stage`.
+    // The loads of a stage are issued one at a time between matrix instructions: the texture
+    // addresser takes a wave-wide 1 KiB request every ~16 cycles and a wave stalls at a request
+    // that finds it busy, so a burst of requests from all waves would leave the matrix cores idle.
+    auto gload_one = [&](int kt, int stage, auto n_tag) {
+        constexpr int n = decltype(n_tag)::value;
         const uint32_t base = lds0 + stage * L::kStage;
-#pragma unroll
-        for (int s = 0; s < A_PER_W; ++s)
-            lds_dma16(pa[s] + (int64_t)kt * A_ELEMS, base + (wave * A_PER_W + s) * 1024);
-#pragma unroll
-        for (int s = 0; s < B_PER_W; ++s)
+        if constexpr (n < A_PER_W) {
+            lds_dma16(pa[n] + (int64_t)kt * A_ELEMS, base + (wave * A_PER_W + n) * 1024);
+        } else if constexpr (n < A_PER_W + B_PER_W) {
+            constexpr int s = n - A_PER_W;
             lds_dma16(pb[s] + (int64_t)kt * KSTAGE,
                       base + L::kABytes + L::kMetaBytes + (wave * B_PER_W + s) * 1024);
-        if constexpr (SPARSE) lds_dma4(pmeta + (int64_t)kt * 8, base + L::kABytes + wave * 256);
+        } else if constexpr (SPARSE && n == A_PER_W + B_PER_W) {
+            lds_dma4(pmeta + (int64_t)kt * meta_stride, base + L::kABytes + wave * 256);
+        }
+    };
+    auto gload = [&](int kt, int stage) {
+        gload_one(kt, stage, std::integral_constant<int, 0>{});
+        gload_one(kt, stage, std::integral_constant<int, 1>{});
+        gload_one(kt, stage, std::integral_constant<int, 2>{});
+        gload_one(kt, stage, std::integral_constant<int, 3>{});
+        gload_one(kt, stage, std::integral_constant<int, 4>{});
+        gload_one(kt, stage, std::integral_constant<int, 5>{});
+        gload_one(kt, stage, std::integral_constant<int, 6>{});
+        gload_one(kt, stage, std::integral_constant<int, 7>{});
     };
     constexpr int LOADS_PER_STAGE = A_PER_W + B_PER_W + (SPARSE ? 1 : 0);
+    static_assert(LOADS_PER_STAGE <= 8 && LOADS_PER_STAGE <= TM * TN, "loads are paired with matrix instructions");
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 acc[TM][TN];
@@ -231,27 +245,40 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
                 ix[i] = *reinterpret_cast<const int*>(bM + (arow0 + i * 32) * 8 + kb * 4);
         }
     };
-    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag) {
+    auto mma_one = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto n_tag) {
         constexpr int SUB = decltype(sub_tag)::value;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                if constexpr (SPARSE)
-                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[i].v, f.b[j].v, acc[i][j],
-                                                                          ix[i], 0, SUB);
-                else
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i].v, bf16x8(f.b[j].v.lo),
-                                                                        acc[i][j], 0, 0, 0);
-            }
+        constexpr int n = decltype(n_tag)::value, i = n % TM, j = n / TM;
+        if constexpr (n < TM * TN) {
+            if constexpr (SPARSE)
+                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[i].v, f.b[j].v, acc[i][j],
+                                                                      ix[i], 0, SUB);
+            else
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i].v, bf16x8(f.b[j].v.lo),
+                                                                    acc[i][j], 0, 0, 0);
+        }
+    };
+    // matrix work of one sub-step; with LOAD, request n of stage kt_load follows instruction n
+    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto load_tag, int kt_load, int buf) {
+        constexpr bool LOAD = decltype(load_tag)::value;
+        static_assert(TM * TN <= 16, "unrolled by hand up to 16 matrix instructions");
+#define RTL_MMA_STEP(N)                                                             \
+        mma_one(f, ix, sub_tag, std::integral_constant<int, N>{});                  \
+        if constexpr (LOAD && N < LOADS_PER_STAGE) {                                \
+            gload_one(kt_load, buf, std::integral_constant<int, N>{});              \
+            __builtin_amdgcn_sched_barrier(0);                                      \
+        }
+        RTL_MMA_STEP(0) RTL_MMA_STEP(1) RTL_MMA_STEP(2) RTL_MMA_STEP(3)
+        RTL_MMA_STEP(4) RTL_MMA_STEP(5) RTL_MMA_STEP(6) RTL_MMA_STEP(7)
+        RTL_MMA_STEP(8) RTL_MMA_STEP(9) RTL_MMA_STEP(10) RTL_MMA_STEP(11)
+        RTL_MMA_STEP(12) RTL_MMA_STEP(13) RTL_MMA_STEP(14) RTL_MMA_STEP(15)
+#undef RTL_MMA_STEP
     };
 
-    // ---- prologue: STAGES-1 stages in flight, first one visible ------------------------------
+    // ---- prologue: the whole ring in flight, stage 0 visible ----------------------------------
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
+    for (int s = 0; s < STAGES; ++s)
         if (s < KT) gload(s, s);
-    // wait for stage 0 only: the later STAGES-2 stages may stay in flight
-    if (KT >= STAGES - 1) wait_vmcnt_lgkm0<(STAGES - 2) * LOADS_PER_STAGE>();
+    if (KT >= STAGES) wait_vmcnt_lgkm0<(STAGES - 1) * LOADS_PER_STAGE>();
     else wait_vmcnt_lgkm0<0>();
     __builtin_amdgcn_s_barrier();
 
@@ -260,30 +287,31 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     read_idx(0, ix_cur);
     wait_vmcnt_lgkm0<63>();            // fragments of sub-step 0 are in registers
 
-    // One stage of the main loop. HAS_LOAD: a stage STAGES-1 ahead exists and is requested now;
-    // HAS_NEXT: stage kt+1 exists and its first fragments are fetched behind the barrier.
+    // One stage of the main loop. Schedule inside a stage:
+    //   read fragments of sub-step 1 | matrix work of sub-step 0 |
+    //   wait: own reads of this stage done, stage kt+1 landed | barrier |
+    //   read fragments of stage kt+1 sub-step 0, refill the buffer of stage kt with stage
+    //   kt+STAGES | matrix work of sub-step 1
+    // so every stage has two full stage times to arrive and STAGES-1 stages are in flight.
+    // PENDING: stages younger than kt+1 still in flight at the wait (compile-time per loop phase).
     int cur = 0;                       // LDS buffer of stage kt
-    auto stage_step = [&](int kt, auto has_load, auto has_next) {
+    auto stage_step = [&](int kt, auto has_load, auto has_next, auto pending) {
         constexpr bool HAS_LOAD = decltype(has_load)::value, HAS_NEXT = decltype(has_next)::value;
+        constexpr int PENDING = decltype(pending)::value;
         const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
-        const int pre = cur == 0 ? STAGES - 1 : cur - 1;   // buffer of stage kt + STAGES - 1
-        // fragments of sub-step 1 and the stage STAGES-1 ahead start moving, then sub-step 0 runs
         read_frags(cur, 1, f1);
-        if constexpr (HAS_LOAD) gload(kt + STAGES - 1, pre);
         __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the matrix work
-        mma(f0, ix_cur, std::integral_constant<int, 0>{});
+        mma(f0, ix_cur, std::integral_constant<int, 0>{}, std::false_type{}, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        // stage kt+1 must have landed, and this wave's reads of stage kt must be done, before the
-        // barrier lets anyone read stage kt+1 or overwrite stage kt
-        if constexpr (HAS_LOAD) wait_vmcnt_lgkm0<(STAGES - 2) * LOADS_PER_STAGE>();
-        else wait_vmcnt_lgkm0<0>();
+        wait_vmcnt_lgkm0<PENDING * LOADS_PER_STAGE>();
         __builtin_amdgcn_s_barrier();
         if constexpr (HAS_NEXT) {
             read_frags(nxt, 0, f0);
             read_idx(nxt, ix_nxt);
         }
         __builtin_amdgcn_sched_barrier(0);
-        mma(f1, ix_cur, std::integral_constant<int, 1>{});
+        mma(f1, ix_cur, std::integral_constant<int, 1>{}, std::integral_constant<bool, HAS_LOAD>{},
+            kt + STAGES, cur);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (SPARSE && HAS_NEXT) {
 #pragma unroll
@@ -291,11 +319,20 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         }
         cur = nxt;
     };
-    const int n_main = KT - (STAGES - 1);
+    static_assert(STAGES == 2 || STAGES == 3 || STAGES == 4, "ring depth");
     int kt = 0;
-    for (; kt < n_main; ++kt) stage_step(kt, std::true_type{}, std::true_type{});
-    for (; kt < KT - 1; ++kt) stage_step(kt, std::false_type{}, std::true_type{});
-    stage_step(kt, std::false_type{}, std::false_type{});
+    // steady state: stages kt+1 .. kt+STAGES-1 are in flight at the wait
+    for (; kt < KT - STAGES; ++kt)
+        stage_step(kt, std::true_type{}, std::true_type{}, std::integral_constant<int, STAGES - 2>{});
+    // drain: nothing new is requested; fewer stages remain in flight each step
+    if constexpr (STAGES >= 4) {
+        if (kt < KT - 3) { stage_step(kt, std::false_type{}, std::true_type{}, std::integral_constant<int, 2>{}); ++kt; }
+    }
+    if constexpr (STAGES >= 3) {
+        if (kt < KT - 2) { stage_step(kt, std::false_type{}, std::true_type{}, std::integral_constant<int, 1>{}); ++kt; }
+    }
+    if (kt < KT - 1) { stage_step(kt, std::false_type{}, std::true_type{}, std::integral_constant<int, 0>{}); ++kt; }
+    stage_step(kt, std::false_type{}, std::false_type{}, std::integral_constant<int, 0>{});
 
     // ---- epilogue: optional fp32 scales, bias, bf16 RNE store -------------------------------
     const float ts = a.tensor_scale ? a.tensor_scale[0] : 1.0f;

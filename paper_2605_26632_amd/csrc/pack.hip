@@ -85,14 +85,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int COMP>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     const uint16_t* __restrict__ X, int64_t M, int K, int64_t ldx, float eps,
-    uint16_t* __restrict__ vals, uint8_t* __restrict__ meta, float* __restrict__ scale,
-    float* __restrict__ rowsums) {
+    uint16_t* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ meta_km,
+    int64_t Mpad, float* __restrict__ scale, float* __restrict__ rowsums) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     if (row >= M) return;  // whole wave leaves together
     const uint16_t* xr = X + row * ldx;
     uint16_t* vr = vals + row * (int64_t)(K / 2);
-    uint8_t* mr = meta + row * (int64_t)(K / 8);
+    uint8_t* mr = meta + row * (int64_t)(K / 8);          // only dereferenced when meta != null
+    uint8_t* kmr = meta_km + row * 8;                      // only dereferenced when meta_km != null
     float num = 0.f, den = 0.f;
     // rows of metadata are K/8 bytes: whole 32-bit words only when K is a multiple of 32
     const bool word_meta = (K & 31) == 0;
@@ -119,11 +120,16 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
                                (quad_bcast<0xFF>(b) << 24);
             if (k < K) {
                 *reinterpret_cast<uint2*>(vr + k / 2) = make_uint2(g0.packed, g1.packed);
-                if (word_meta) {
-                    if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(mr + k / 8) = w;
-                } else {
-                    mr[k / 8] = (uint8_t)b;
+                if (meta) {
+                    if (word_meta) {
+                        if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(mr + k / 8) = w;
+                    } else {
+                        mr[k / 8] = (uint8_t)b;
+                    }
                 }
+                // k-major twin: the quad's word is half of the row's 8-byte record of block k / 64
+                if (meta_km && (lane & 3) == 0)
+                    *reinterpret_cast<uint32_t*>(kmr + (int64_t)(k >> 6) * Mpad * 8 + ((k >> 5) & 1) * 4) = w;
             }
         }
     }
@@ -164,29 +170,49 @@ __global__ __launch_bounds__(256) void tensor_scale_kernel(const float* __restri
     if (threadIdx.x == 0) scale[0] = (float)sqrt(sn[0] / (sd[0] + (double)eps));
 }
 
+// One thread per (row, 64-k block): rows run fastest so the k-major writes are contiguous.
+__global__ __launch_bounds__(256) void meta_to_kmajor_kernel(const uint8_t* __restrict__ meta,
+                                                             int64_t M, int64_t KB, int64_t Mpad,
+                                                             uint8_t* __restrict__ km) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= M * KB) return;
+    const int64_t row = t % M, kb = t / M;
+    const uint2 v = *reinterpret_cast<const uint2*>(meta + row * KB * 8 + kb * 8);
+    *reinterpret_cast<uint2*>(km + (kb * Mpad + row) * 8) = v;
+}
+
 }  // namespace
 
+hipError_t launch_meta_to_kmajor(const uint8_t* meta, int64_t M, int64_t K, uint8_t* meta_km,
+                                 hipStream_t stream) {
+    const int64_t KB = K / 64, n = M * KB;
+    hipLaunchKernelGGL(meta_to_kmajor_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                       meta, M, KB, kmajor_rows(M), meta_km);
+    return hipGetLastError();
+}
+
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
-                                float eps, uint16_t* vals, uint8_t* meta, float* scale,
-                                float* rowsums, hipStream_t stream) {
+                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* meta_km,
+                                float* scale, float* rowsums, hipStream_t stream) {
+    const int64_t Mpad = kmajor_rows(M);
     const dim3 grid((unsigned)((M + kWavesPerBlock - 1) / kWavesPerBlock));
     const dim3 block(kWavesPerBlock * 64);
     switch (comp) {
         case RTL_COMP_NONE:
             hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_NONE>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, scale, rowsums);
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
             break;
         case RTL_COMP_GROUP:
             hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_GROUP>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, scale, rowsums);
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
             break;
         case RTL_COMP_ROW:
             hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_ROW>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, scale, rowsums);
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
             break;
         case RTL_COMP_TENSOR:
             hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_TENSOR>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, scale, rowsums);
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
             hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps,
                                scale);
             break;

@@ -7,17 +7,30 @@
 
 namespace rtl {
 
+// ---- metadata layouts -----------------------------------------------------------------------
+// canonical (ABI): meta[M][K/8] bytes, row-major.
+// k-major (what the GEMM streams): for every block of 64 dense k, one 8-byte record per row,
+// records of a block contiguous over rows: km[(k / 64) * Mpad + m] (8 bytes), Mpad = kmajor_rows(M).
+// A 256-row tile of one block is then a single contiguous 2 KiB run instead of 256 scattered
+// 8-byte pieces, which keeps the L2 -> CU traffic of the GEMM at its algorithmic size.
+inline int64_t kmajor_rows(int64_t M) { return (M + 255) / 256 * 256; }
+inline size_t kmajor_bytes(int64_t M, int64_t K) { return (size_t)(K / 64) * (size_t)kmajor_rows(M) * 8; }
+
 // ---- sparsify + pack (pack.hip) -------------------------------------------------------------
-// Launches the select/compensate/compress sweep. `rowsums` ([M][2] fp32) is only touched for
-// RTL_COMP_TENSOR. Returns the HIP launch status.
+// Launches the select/compensate/compress sweep. `meta` (canonical) and `meta_km` (k-major, needs
+// K % 64 == 0) are each optional; `rowsums` ([M][2] fp32) is only touched for RTL_COMP_TENSOR.
+// Returns the HIP launch status.
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
-                                float eps, uint16_t* vals, uint8_t* meta, float* scale,
-                                float* rowsums, hipStream_t stream);
+                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* meta_km,
+                                float* scale, float* rowsums, hipStream_t stream);
+// canonical -> k-major copy of the metadata (K % 64 == 0).
+hipError_t launch_meta_to_kmajor(const uint8_t* meta, int64_t M, int64_t K, uint8_t* meta_km,
+                                 hipStream_t stream);
 
 // ---- GEMMs (gemm.hip) -----------------------------------------------------------------------
 struct GemmArgs {
     const uint16_t* A;      // dense: X [M,K] (lda); sparse: vals [M,K/2] (lda = K/2)
-    const uint8_t* meta;    // sparse only: [M,K/8]
+    const uint8_t* meta;    // sparse only: k-major records, kmajor_rows(M) rows per block
     const uint16_t* W;      // [N,K] (ldw)
     const uint16_t* bias;   // nullable [N]
     const float* row_scale; // nullable [M]
