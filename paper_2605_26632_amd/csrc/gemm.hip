@@ -70,13 +70,19 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0() {   // vmcnt <= N, all LDS re
 
 // Per-stage LDS footprint. Rows of the A tile hold 64 bytes in both kernels (32 kept bf16 of 64
 // dense k, or 32 dense k); rows of the B tile hold 128 bytes (sparse) or 64 bytes (dense).
-template <bool SPARSE, int BM, int BN, int STAGES>
+template <bool SPARSE, int BM, int BN, int STAGES, int WAVES_M = 1, int WAVES_N = 1>
 struct Smem {
     static constexpr int kABytes = BM * 64;
     static constexpr int kMetaBytes = SPARSE ? BM * 8 : 0;
     static constexpr int kBBytes = SPARSE ? BN * 128 : BN * 64;
     static constexpr int kStage = kABytes + kMetaBytes + kBBytes;
-    static constexpr int kTotal = STAGES * kStage;
+    static constexpr int kRing = STAGES * kStage;
+    // epilogue staging: every wave owns (BM / WAVES_M) rows of (BN / WAVES_N) bf16 plus 16 bytes
+    // of padding per row (keeps rows 4 apart, written together, in different banks)
+    static constexpr int kEpiRowBytes = (BN / WAVES_N) * 2 + 16;
+    static constexpr int kEpi = WAVES_M * WAVES_N * (BM / WAVES_M) * kEpiRowBytes;
+    static constexpr int kTotal = kRing > kEpi ? kRing : kEpi;
+    static_assert(kTotal <= 160 * 1024, "LDS budget of a CU");
 };
 
 // LDS swizzles. A 16-byte read of a wave is served 16 lanes at a time over 64 four-byte banks, so
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
-    using L = Smem<SPARSE, BM, BN, STAGES>;
+    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N>;
     constexpr int KSTAGE = SPARSE ? 64 : 32;          // dense k per stage
     constexpr int A_ELEMS = 32;                       // bf16 of an A row per stage (both kernels)
     // one wave-wide direct-to-LDS load moves 64 chunks of 16 bytes = 1 KiB
@@ -198,7 +204,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         gload_one(kt, stage, std::integral_constant<int, 7>{});
     };
     constexpr int LOADS_PER_STAGE = A_PER_W + B_PER_W + (SPARSE ? 1 : 0);
-    static_assert(LOADS_PER_STAGE <= 8 && LOADS_PER_STAGE <= TM * TN, "loads are paired with matrix instructions");
+    static_assert(LOADS_PER_STAGE <= 8 && (LOADS_PER_STAGE + 1) / 2 <= TM * TN, "loads are paired with matrix instructions");
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 acc[TM][TN];
@@ -257,14 +263,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
                                                                     acc[i][j], 0, 0, 0);
         }
     };
-    // matrix work of one sub-step; with LOAD, request n of stage kt_load follows instruction n
-    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto load_tag, int kt_load, int buf) {
-        constexpr bool LOAD = decltype(load_tag)::value;
-        static_assert(TM * TN <= 16, "unrolled by hand up to 16 matrix instructions");
+    // matrix work of one sub-step; requests LO <= n < HI of stage kt_load (ring buffer buf) are
+    // issued one after each matrix instruction
+    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto lo_tag, auto hi_tag,
+                   int kt_load, int buf) {
+        constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
+        static_assert(TM * TN <= 16 && HI - LO <= TM * TN, "unrolled by hand up to 16 matrix instructions");
 #define RTL_MMA_STEP(N)                                                             \
         mma_one(f, ix, sub_tag, std::integral_constant<int, N>{});                  \
-        if constexpr (LOAD && N < LOADS_PER_STAGE) {                                \
-            gload_one(kt_load, buf, std::integral_constant<int, N>{});              \
+        if constexpr (LO + N < HI) {                                                \
+            gload_one(kt_load, buf, std::integral_constant<int, LO + N>{});         \
             __builtin_amdgcn_sched_barrier(0);                                      \
         }
         RTL_MMA_STEP(0) RTL_MMA_STEP(1) RTL_MMA_STEP(2) RTL_MMA_STEP(3)
@@ -287,21 +295,31 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     read_idx(0, ix_cur);
     wait_vmcnt_lgkm0<63>();            // fragments of sub-step 0 are in registers
 
-    // One stage of the main loop. Schedule inside a stage:
-    //   read fragments of sub-step 1 | matrix work of sub-step 0 |
-    //   wait: own reads of this stage done, stage kt+1 landed | barrier |
-    //   read fragments of stage kt+1 sub-step 0, refill the buffer of stage kt with stage
-    //   kt+STAGES | matrix work of sub-step 1
-    // so every stage has two full stage times to arrive and STAGES-1 stages are in flight.
-    // PENDING: stages younger than kt+1 still in flight at the wait (compile-time per loop phase).
+    // One stage of the main loop. Schedule inside a stage kt:
+    //   read fragments of sub-step 1 |
+    //   matrix work of sub-step 0, interleaved with the second part of the requests of stage
+    //   kt+STAGES-1 (its buffer, the one of stage kt-1, was released by the previous barrier) |
+    //   wait: own reads of stage kt done, stage kt+1 landed | barrier |
+    //   read fragments of stage kt+1 sub-step 0 |
+    //   matrix work of sub-step 1, interleaved with the first part of the requests of stage
+    //   kt+STAGES (into the buffer of stage kt, which nobody reads any more).
+    // Every stage has about two stage times to arrive and the request stream never bursts.
+    // PENDING: whole stages younger than kt+1 in flight at the wait (compile-time per phase).
+    constexpr int SPLIT = (LOADS_PER_STAGE + 1) / 2;   // requests issued in the second half
+    using c0 = std::integral_constant<int, 0>;
+    using cS = std::integral_constant<int, SPLIT>;
+    using cL = std::integral_constant<int, LOADS_PER_STAGE>;
     int cur = 0;                       // LDS buffer of stage kt
-    auto stage_step = [&](int kt, auto has_load, auto has_next, auto pending) {
-        constexpr bool HAS_LOAD = decltype(has_load)::value, HAS_NEXT = decltype(has_next)::value;
+    auto stage_step = [&](int kt, auto load_a, auto load_b, auto has_next, auto pending) {
+        constexpr bool LOAD_A = decltype(load_a)::value, LOAD_B = decltype(load_b)::value;
+        constexpr bool HAS_NEXT = decltype(has_next)::value;
         constexpr int PENDING = decltype(pending)::value;
         const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+        const int prv = cur == 0 ? STAGES - 1 : cur - 1;
         read_frags(cur, 1, f1);
         __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the matrix work
-        mma(f0, ix_cur, std::integral_constant<int, 0>{}, std::false_type{}, 0, 0);
+        if constexpr (LOAD_A) mma(f0, ix_cur, c0{}, cS{}, cL{}, kt + STAGES - 1, prv);
+        else mma(f0, ix_cur, c0{}, c0{}, c0{}, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         wait_vmcnt_lgkm0<PENDING * LOADS_PER_STAGE>();
         __builtin_amdgcn_s_barrier();
@@ -310,8 +328,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
             read_idx(nxt, ix_nxt);
         }
         __builtin_amdgcn_sched_barrier(0);
-        mma(f1, ix_cur, std::integral_constant<int, 1>{}, std::integral_constant<bool, HAS_LOAD>{},
-            kt + STAGES, cur);
+        if constexpr (LOAD_B) mma(f1, ix_cur, std::integral_constant<int, 1>{}, c0{}, cS{}, kt + STAGES, cur);
+        else mma(f1, ix_cur, std::integral_constant<int, 1>{}, c0{}, c0{}, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (SPARSE && HAS_NEXT) {
 #pragma unroll
@@ -320,38 +338,95 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         cur = nxt;
     };
     static_assert(STAGES == 2 || STAGES == 3 || STAGES == 4, "ring depth");
+    using T = std::true_type;
+    using F = std::false_type;
+    using P = std::integral_constant<int, STAGES - 2>;
     int kt = 0;
-    // steady state: stages kt+1 .. kt+STAGES-1 are in flight at the wait
-    for (; kt < KT - STAGES; ++kt)
-        stage_step(kt, std::true_type{}, std::true_type{}, std::integral_constant<int, STAGES - 2>{});
-    // drain: nothing new is requested; fewer stages remain in flight each step
+    if (KT > STAGES) {
+        // stage 0 has no half-requested predecessor; from then on both halves carry requests
+        stage_step(kt, F{}, T{}, T{}, P{});
+        for (kt = 1; kt < KT - STAGES; ++kt) stage_step(kt, T{}, T{}, T{}, P{});
+        // second part of the last stage; nothing new afterwards
+        stage_step(kt, T{}, F{}, T{}, P{});
+        ++kt;
+    }
+    // drain (and short K): stages kt+1 .. KT-1 are all requested; fewer remain in flight each step
     if constexpr (STAGES >= 4) {
-        if (kt < KT - 3) { stage_step(kt, std::false_type{}, std::true_type{}, std::integral_constant<int, 2>{}); ++kt; }
+        if (kt == KT - 4) { stage_step(kt, F{}, F{}, T{}, std::integral_constant<int, 2>{}); ++kt; }
     }
     if constexpr (STAGES >= 3) {
-        if (kt < KT - 2) { stage_step(kt, std::false_type{}, std::true_type{}, std::integral_constant<int, 1>{}); ++kt; }
+        if (kt == KT - 3) { stage_step(kt, F{}, F{}, T{}, std::integral_constant<int, 1>{}); ++kt; }
     }
-    if (kt < KT - 1) { stage_step(kt, std::false_type{}, std::true_type{}, std::integral_constant<int, 0>{}); ++kt; }
-    stage_step(kt, std::false_type{}, std::false_type{}, std::integral_constant<int, 0>{});
+    if (kt == KT - 2) { stage_step(kt, F{}, F{}, T{}, std::integral_constant<int, 0>{}); ++kt; }
+    stage_step(kt, F{}, F{}, F{}, std::integral_constant<int, 0>{});
 
-    // ---- epilogue: optional fp32 scales, bias, bf16 RNE store -------------------------------
+    // ---- epilogue: optional fp32 scales, bias, bf16 RNE, store --------------------------------
     const float ts = a.tensor_scale ? a.tensor_scale[0] : 1.0f;
+    auto finish = [&](float v, int64_t row, float bv) {
+        if (a.row_scale) v *= a.row_scale[row];
+        if (a.tensor_scale) v *= ts;
+        if (a.bias) v += bv;
+        return (uint16_t)f32_to_bf16_rne(v);
+    };
+    const bool wide_ok = ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0) && (a.ldy % 8 == 0);
+    if (wide_ok) {
+        // The accumulator layout gives a lane one column and scattered rows, i.e. 2-byte stores.
+        // Each wave therefore transposes its tile through a private LDS region (the ring is no
+        // longer needed) and writes whole 16-byte row segments.
+        constexpr int ROWB = L::kEpiRowBytes;
+        wait_vmcnt_lgkm0<0>();
+        __builtin_amdgcn_s_barrier();     // every wave is done reading the ring
+        uint8_t* ep = smem + wave * (WTM * ROWB);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int64_t col = n0 + wn * WTN + j * 32 + li;
-        if (col >= a.N) continue;
-        const float bv = a.bias ? __uint_as_float((uint32_t)a.bias[col] << 16) : 0.f;
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = min(n0 + wn * WTN + j * 32 + li, a.N - 1);
+            const float bv = a.bias ? __uint_as_float((uint32_t)a.bias[col] << 16) : 0.f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
-                if (row >= a.M) continue;
-                float v = acc[i][j][r];
-                if (a.row_scale) v *= a.row_scale[row];
-                if (a.tensor_scale) v *= ts;
-                if (a.bias) v += bv;
-                a.Y[row * a.ldy + col] = (uint16_t)f32_to_bf16_rne(v);
+                for (int r = 0; r < 16; ++r) {
+                    const int rl = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
+                    const int64_t row = min(m0 + wm * WTM + rl, a.M - 1);
+                    *reinterpret_cast<uint16_t*>(ep + rl * ROWB + (j * 32 + li) * 2) =
+                        finish(acc[i][j][r], row, bv);
+                }
+        }
+        // same wave reads back what it wrote: LDS operations of a wave complete in order
+        constexpr int CPR = WTN / 8;               // 16-byte chunks per tile row
+        constexpr int CHUNKS = WTM * CPR;
+#pragma unroll
+        for (int q0 = 0; q0 < CHUNKS; q0 += 64) {
+            const int q = q0 + lane;
+            if (q < CHUNKS) {
+                const int rl = q / CPR, c = q % CPR;
+                const int64_t row = m0 + wm * WTM + rl, col = n0 + wn * WTN + c * 8;
+                if (row < a.M && col < a.N) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(ep + rl * ROWB + c * 16);
+                    uint16_t* dst = a.Y + row * a.ldy + col;
+                    if (col + 8 <= a.N) {
+                        *reinterpret_cast<uint4*>(dst) = v;
+                    } else {
+                        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                        for (int e = 0; e < 8 && col + e < a.N; ++e)
+                            dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                    }
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = n0 + wn * WTN + j * 32 + li;
+            if (col >= a.N) continue;
+            const float bv = a.bias ? __uint_as_float((uint32_t)a.bias[col] << 16) : 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = m0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
+                    if (row >= a.M) continue;
+                    a.Y[row * a.ldy + col] = finish(acc[i][j][r], row, bv);
+                }
             }
         }
     }
@@ -359,7 +434,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
 
 template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
-    using L = Smem<SPARSE, BM, BN, STAGES>;
+    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N>;
     auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES>;
     static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
     if (!attr_set) {
@@ -377,8 +452,23 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
 
 size_t gemm_workspace_bytes(bool, int64_t, int64_t, int64_t) { return 0; }
 
+// Tile choice for the sparse kernel. The main loop is bound by the rate at which a CU can pull
+// operand stages out of L2, so a tile costs about (bytes per stage) and a launch costs
+// ceil(tiles / CUs) rounds of that: 256x256 moves 51 KB per stage, 256x192 moves 43 KB but
+// yields a third more tiles, which pays when it turns a 3/4-full round into a full one.
+static bool prefer_192(int64_t M, int64_t N) {
+    constexpr int64_t kCUs = 256;
+    const int64_t tm = (M + 255) / 256;
+    const int64_t t256 = tm * ((N + 255) / 256), t192 = tm * ((N + 191) / 192);
+    const int64_t c256 = (t256 + kCUs - 1) / kCUs * 51, c192 = (t192 + kCUs - 1) / kCUs * 43;
+    return c192 < c256;
+}
+
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
-    if (sparse) return launch_cfg<true, 256, 256, 2, 4, 3>(a, stream);
+    if (sparse) {
+        if (prefer_192(a.M, a.N)) return launch_cfg<true, 256, 192, 4, 2, 3>(a, stream);
+        return launch_cfg<true, 256, 256, 2, 4, 3>(a, stream);
+    }
     return launch_cfg<false, 256, 256, 2, 4, 3>(a, stream);
 }
 
