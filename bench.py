@@ -19,9 +19,10 @@ sys.path.insert(0, ROOT)
 WORKLOAD = "mlp_down"          # benchmark configs[1]
 DENSE_BF16_PEAK_TFLOPS = 2500.0  # published dense bf16 MFMA peak; SMFMAC issues at this rate
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per sparse-GEMM launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs recorded
-# under profiles/ (None until measured for the current kernel).
-GEMM_TRAFFIC_BYTES = None
+# HBM-side bytes per sparse-GEMM launch on the default workload, from the rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_kernel_sparse_mlp_down.md
+# (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 KiB after calibration against a plain 1 GiB copy).
+GEMM_TRAFFIC_BYTES = {"mlp_down": int((188181 * 2.0 + 24576 * 1.0) * 1024)}
 
 
 def event_times(fn, steps, warmup, torch):
@@ -46,6 +47,9 @@ def main():
     ap.add_argument("--comp", default="group", choices=["none", "group", "row", "tensor"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy (3 launches): reference for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path has no "
@@ -61,6 +65,15 @@ def main():
         sys.exit(2)
     rtl.lib()  # raises if the HIP library is not built: there is no fallback
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4,
+                          "calibrate_copy_bytes_written": src.numel() * 4, "launches": 3}))
+        return
     comp = rtl.COMP[args.comp]
     X, W = synth.workload(args.workload, seed=0, device=dev)
     M, K = X.shape
@@ -105,7 +118,7 @@ def main():
         "kernel": "gemm_kernel<sparse> (v_smfmac_f32_32x32x32_bf16)",
         "bound": "mfma", "achieved": round(achieved, 1), "peak": DENSE_BF16_PEAK_TFLOPS,
         "unit": "TFLOP/s", "frac": round(achieved / DENSE_BF16_PEAK_TFLOPS, 4),
-        "traffic": GEMM_TRAFFIC_BYTES,
+        "traffic": GEMM_TRAFFIC_BYTES.get(args.workload) if args.comp == "group" else None,
         "note": "achieved = executed flops M*N*K per launch / mean launch time; the same fraction "
                 "holds for effective 2MNK flops against the 2:4 peak (2x dense)",
         "avg_launch_ms": round(gemm_ms, 4),
