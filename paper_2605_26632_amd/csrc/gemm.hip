@@ -134,7 +134,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     static_assert(A_LOADS % NW == 0 && B_LOADS % NW == 0, "tile loads must divide over the waves");
     constexpr int A_PER_W = A_LOADS / NW, B_PER_W = B_LOADS / NW;
     constexpr int M_LOADS = SPARSE ? (BM * 8) / 256 : 0;  // metadata: 4 bytes per lane per load
-    static_assert(!SPARSE || M_LOADS == NW, "one metadata load per wave");
+    static_assert(!SPARSE || M_LOADS % NW == 0, "metadata loads must divide over the waves");
+    constexpr int M_PER_W = M_LOADS / NW;
 
     extern __shared__ __align__(16) uint8_t smem[];
 
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     if constexpr (SPARSE) {
         // k-major records: the 256 rows of this tile are one contiguous 2 KiB run per stage and
         // wave w moves its 256-byte share (rows 32 w .. 32 w + 31), 4 bytes per lane
-        pmeta = a.meta + (m0 + wave * 32) * 8 + lane * 4;
+        pmeta = a.meta + (m0 + wave * (32 * M_PER_W)) * 8 + lane * 4;
     }
 
     const int64_t meta_stride = ((a.M + 255) / 256 * 256) * 8;   // bytes between 64-k blocks
@@ -189,8 +190,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
             constexpr int s = n - A_PER_W;
             lds_dma16(pb[s] + (int64_t)kt * KSTAGE,
                       base + L::kABytes + L::kMetaBytes + (wave * B_PER_W + s) * 1024);
-        } else if constexpr (SPARSE && n == A_PER_W + B_PER_W) {
-            lds_dma4(pmeta + (int64_t)kt * meta_stride, base + L::kABytes + wave * 256);
+        } else if constexpr (SPARSE && n < A_PER_W + B_PER_W + M_PER_W) {
+            constexpr int s = n - A_PER_W - B_PER_W;
+            lds_dma4(pmeta + (int64_t)kt * meta_stride + s * 256,
+                     base + L::kABytes + (wave * M_PER_W + s) * 256);
         }
     };
     auto gload = [&](int kt, int stage) {
@@ -202,9 +205,17 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         gload_one(kt, stage, std::integral_constant<int, 5>{});
         gload_one(kt, stage, std::integral_constant<int, 6>{});
         gload_one(kt, stage, std::integral_constant<int, 7>{});
+        gload_one(kt, stage, std::integral_constant<int, 8>{});
+        gload_one(kt, stage, std::integral_constant<int, 9>{});
+        gload_one(kt, stage, std::integral_constant<int, 10>{});
+        gload_one(kt, stage, std::integral_constant<int, 11>{});
+        gload_one(kt, stage, std::integral_constant<int, 12>{});
+        gload_one(kt, stage, std::integral_constant<int, 13>{});
+        gload_one(kt, stage, std::integral_constant<int, 14>{});
+        gload_one(kt, stage, std::integral_constant<int, 15>{});
     };
-    constexpr int LOADS_PER_STAGE = A_PER_W + B_PER_W + (SPARSE ? 1 : 0);
-    static_assert(LOADS_PER_STAGE <= 8 && (LOADS_PER_STAGE + 1) / 2 <= TM * TN, "loads are paired with matrix instructions");
+    constexpr int LOADS_PER_STAGE = A_PER_W + B_PER_W + (SPARSE ? M_PER_W : 0);
+    static_assert(LOADS_PER_STAGE <= 16 && (LOADS_PER_STAGE + 1) / 2 <= TM * TN, "loads are paired with matrix instructions");
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 acc[TM][TN];
@@ -251,6 +262,27 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
                 ix[i] = *reinterpret_cast<const int*>(bM + (arow0 + i * 32) * 8 + kb * 4);
         }
     };
+    // Read number n of the fragment set of (stage, SUB), in the order the matrix instructions need
+    // them: metadata words (sub-step 0 only), A fragments, then B fragments column block by block.
+    auto read_one = [&](int stage, auto sub_tag, Frags& f, int (&ix)[TM], auto n_tag) {
+        constexpr int SUB = decltype(sub_tag)::value, n = decltype(n_tag)::value;
+        constexpr int NI = (SPARSE && SUB == 0) ? TM : 0;     // metadata reads first
+        const uint8_t* base = smem + stage * L::kStage;
+        const uint8_t* bB = base + L::kABytes + L::kMetaBytes;
+        if constexpr (n < NI) {
+            ix[n] = *reinterpret_cast<const int*>(base + L::kABytes + (arow0 + n * 32) * 8 + kb * 4);
+        } else if constexpr (n < NI + TM) {
+            constexpr int i = n - NI;
+            f.a[i].u = *reinterpret_cast<const uint4*>(
+                base + swz4(arow0 + i * 32, SPARSE ? 2 * kb + SUB : 2 * SUB + kb));
+        } else if constexpr (SPARSE && n < NI + TM + 2 * TN) {
+            constexpr int m = n - NI - TM, j = m / 2, h = m % 2;
+            f.b[j].u[h] = *reinterpret_cast<const uint4*>(bB + swz8(brow0 + j * 32, 4 * h + 2 * SUB + kb));
+        } else if constexpr (!SPARSE && n < TM + TN) {
+            constexpr int j = n - TM;
+            f.b[j].u[0] = *reinterpret_cast<const uint4*>(bB + swz4(brow0 + j * 32, 2 * SUB + kb));
+        }
+    };
     auto mma_one = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto n_tag) {
         constexpr int SUB = decltype(sub_tag)::value;
         constexpr int n = decltype(n_tag)::value, i = n % TM, j = n / TM;
@@ -263,17 +295,30 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
                                                                     acc[i][j], 0, 0, 0);
         }
     };
-    // matrix work of one sub-step; requests LO <= n < HI of stage kt_load (ring buffer buf) are
-    // issued one after each matrix instruction
-    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto lo_tag, auto hi_tag,
-                   int kt_load, int buf) {
+    // Matrix work of sub-step SUB on fragments f. After each matrix instruction the wave issues two
+    // LDS reads of the NEXT fragment set (rstage, RSUB) into rf / rix (when READ), and one of the
+    // ring-refill requests LO <= n < HI of stage kt_load into ring buffer buf. Spreading both keeps
+    // the LDS command queue and the texture addresser from filling up, which would stall the wave
+    // in front of its next matrix instruction.
+    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto read_tag, auto rsub_tag,
+                   int rstage, Frags& rf, int (&rix)[TM], auto lo_tag, auto hi_tag, int kt_load, int buf) {
         constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
+        constexpr bool READ = decltype(read_tag)::value;
         static_assert(TM * TN <= 16 && HI - LO <= TM * TN, "unrolled by hand up to 16 matrix instructions");
-#define RTL_MMA_STEP(N)                                                             \
-        mma_one(f, ix, sub_tag, std::integral_constant<int, N>{});                  \
-        if constexpr (LO + N < HI) {                                                \
-            gload_one(kt_load, buf, std::integral_constant<int, LO + N>{});         \
-            __builtin_amdgcn_sched_barrier(0);                                      \
+        static_assert(3 * TM + 2 * TN <= 2 * TM * TN + 2, "two reads per matrix instruction must cover a fragment set");
+#define RTL_MMA_STEP(N)                                                                       \
+        mma_one(f, ix, sub_tag, std::integral_constant<int, N>{});                            \
+        if constexpr (N < TM * TN) {                                                          \
+            if constexpr (READ) {                                                             \
+                read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N>{});     \
+                read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N + 1>{}); \
+                if constexpr (N == TM * TN - 1) {                                             \
+                    read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N + 2>{}); \
+                    read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N + 3>{}); \
+                }                                                                             \
+            }                                                                                 \
+            if constexpr (LO + N < HI) gload_one(kt_load, buf, std::integral_constant<int, LO + N>{}); \
+            __builtin_amdgcn_sched_barrier(0);                                                \
         }
         RTL_MMA_STEP(0) RTL_MMA_STEP(1) RTL_MMA_STEP(2) RTL_MMA_STEP(3)
         RTL_MMA_STEP(4) RTL_MMA_STEP(5) RTL_MMA_STEP(6) RTL_MMA_STEP(7)
@@ -309,6 +354,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     using c0 = std::integral_constant<int, 0>;
     using cS = std::integral_constant<int, SPLIT>;
     using cL = std::integral_constant<int, LOADS_PER_STAGE>;
+    using T = std::true_type;
+    using F = std::false_type;
     int cur = 0;                       // LDS buffer of stage kt
     auto stage_step = [&](int kt, auto load_a, auto load_b, auto has_next, auto pending) {
         constexpr bool LOAD_A = decltype(load_a)::value, LOAD_B = decltype(load_b)::value;
@@ -316,21 +363,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         constexpr int PENDING = decltype(pending)::value;
         const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
         const int prv = cur == 0 ? STAGES - 1 : cur - 1;
-        read_frags(cur, 1, f1);
-        __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of the matrix work
-        if constexpr (LOAD_A) mma(f0, ix_cur, c0{}, cS{}, cL{}, kt + STAGES - 1, prv);
-        else mma(f0, ix_cur, c0{}, c0{}, c0{}, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        using s0 = std::integral_constant<int, 0>;
+        using s1 = std::integral_constant<int, 1>;
+        // sub-step 0 runs while the fragments of sub-step 1 are fetched
+        if constexpr (LOAD_A) mma(f0, ix_cur, s0{}, T{}, s1{}, cur, f1, ix_nxt, cS{}, cL{}, kt + STAGES - 1, prv);
+        else mma(f0, ix_cur, s0{}, T{}, s1{}, cur, f1, ix_nxt, c0{}, c0{}, 0, 0);
         wait_vmcnt_lgkm0<PENDING * LOADS_PER_STAGE>();
         __builtin_amdgcn_s_barrier();
-        if constexpr (HAS_NEXT) {
-            read_frags(nxt, 0, f0);
-            read_idx(nxt, ix_nxt);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (LOAD_B) mma(f1, ix_cur, std::integral_constant<int, 1>{}, c0{}, cS{}, kt + STAGES, cur);
-        else mma(f1, ix_cur, std::integral_constant<int, 1>{}, c0{}, c0{}, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        // sub-step 1 runs while the first fragments (and metadata) of stage kt+1 are fetched
+        if constexpr (LOAD_B) mma(f1, ix_cur, s1{}, std::integral_constant<bool, HAS_NEXT>{}, s0{}, nxt, f0, ix_nxt, c0{}, cS{}, kt + STAGES, cur);
+        else mma(f1, ix_cur, s1{}, std::integral_constant<bool, HAS_NEXT>{}, s0{}, nxt, f0, ix_nxt, c0{}, c0{}, 0, 0);
         if constexpr (SPARSE && HAS_NEXT) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) ix_cur[i] = ix_nxt[i];
@@ -338,8 +380,6 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         cur = nxt;
     };
     static_assert(STAGES == 2 || STAGES == 3 || STAGES == 4, "ring depth");
-    using T = std::true_type;
-    using F = std::false_type;
     using P = std::integral_constant<int, STAGES - 2>;
     int kt = 0;
     if (KT > STAGES) {
