@@ -14,7 +14,7 @@ namespace rtl {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 3;   // 6 and 24 steps per row at K = 3072 / 12288 divide evenly
 
 __device__ __forceinline__ float bits_to_f32(uint32_t u) { return __uint_as_float(u); }
 
@@ -62,9 +62,33 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
         o.num = ((f0 * f0 + f1 * f1) + f2 * f2) + f3 * f3;
         o.den = ka * ka + kb * kb;
         if constexpr (COMP == RTL_COMP_GROUP) {
-            const float s = sqrtf(o.num / (o.den + eps));
-            v0 = f32_to_bf16_rne(s * ka);
-            v1 = f32_to_bf16_rne(s * kb);
+            // The stored values are bf16_rne(s * k) with s = sqrtf(num / den) in IEEE fp32. The
+            // correctly rounded divide and square root cost ~25 instructions, enough to make this
+            // sweep ALU bound, so s is first taken from the 1-ulp hardware reciprocal and square
+            // root: relative to the real value the fast product is off by at most 4.5 and the exact
+            // one by at most 2.5 half-units, so they differ by at most 7 fp32 units. The exact
+            // sequence only runs when a fast product lies within 8 units of a bf16 rounding
+            // boundary, i.e. whenever the two could round differently. The result is bit-identical.
+            const float d = o.den + eps;
+            float s = __builtin_amdgcn_sqrtf(o.num * __builtin_amdgcn_rcpf(d));
+            float p0 = s * ka, p1 = s * kb;
+            const uint32_t l0 = (__float_as_uint(p0) + 8u) & 0xFFFFu;   // window [0x8000-8, 0x8000+8)
+            const uint32_t l1 = (__float_as_uint(p1) + 8u) & 0xFFFFu;
+            const bool near = (l0 - 0x8000u < 16u) | (l1 - 0x8000u < 16u);
+            // tiny (but non-zero) or huge / non-finite scopes are left to the exact sequence too
+            const uint32_t nb = __float_as_uint(o.num);
+            const bool odd_range = (nb - 0x0D800000u >= 0x63800000u) & (nb != 0u);
+            if (near | odd_range) {
+                s = sqrtf(o.num / d);
+                p0 = s * ka;
+                p1 = s * kb;
+            }
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            const f32x2 pp = {p0, p1};
+            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);   // RNE, one instruction on gfx950
+            o.packed = __builtin_bit_cast(uint32_t, pb);
+            return o;
         }
     }
     o.packed = v0 | (v1 << 16);
