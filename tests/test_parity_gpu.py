@@ -170,3 +170,94 @@ def test_zero_sizes_and_error_codes_on_device():
     with pytest.raises(rtl.RtlError) as e:
         rtl.dense_linear(X[:, :32], W[:, :32])       # K = 32 is not a multiple of 64
     assert e.value.status == 2
+
+
+# ------------------------------------------------------------------ full benchmark shapes
+def sampled_rows(M, n, seed):
+    rows = np.sort(np.random.default_rng(seed).choice(M, size=n, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    return rows
+
+
+@pytest.mark.parametrize("name,comp,with_bias", [("qkv", rtl.COMP_ROW, True), ("out_proj", rtl.COMP_TENSOR, False),
+                                                 ("fc2", rtl.COMP_NONE, True), ("hr_out_proj", rtl.COMP_GROUP, False)])
+def test_sparse_linear_full_shapes_all_scopes(name, comp, with_bias):
+    """The remaining layer shapes of the benchmark configs in the launch configuration bench.py
+    uses, every compensation scope, checked on a seeded sample of rows."""
+    X, W = synth.workload(name, seed=1, device=DEV)
+    M, K = X.shape
+    N = W.shape[0]
+    b = synth.bias(N, seed=9, device=DEV, std=0.5) if with_bias else None
+    Y = rtl.sparse_linear(X, W, bias=b, comp=comp)
+    rows = sampled_rows(M, 16, seed=2)
+    sel = torch.from_numpy(rows).to(DEV)
+    Xs, Wb = synth.bits(X[sel]), synth.bits(W)
+    bb = synth.bits(b) if with_bias else None
+    if comp == rtl.COMP_TENSOR:
+        # the tensor-wide factor needs the whole activation; the rows are then independent again
+        Xb = synth.bits(X)
+        s = oracle.scales(Xb, oracle.topk24(Xb), oracle.TENSOR)
+        keep = oracle.topk24(Xs)
+        S, _ = oracle.apply_scales(Xs, keep, s, oracle.TENSOR, operand_round=False)
+        ref = oracle.linear(S, Wb, bb)
+    else:
+        ref = oracle.sparse_linear_oracle(Xs, Wb, bias=bb, scope=comp)["Y"]
+    check_y(Y[sel], ref)
+
+
+def test_pack_high_resolution_activation_masks():
+    """Largest activation of the configs (16896 x 12288): masks, metadata and values, every element."""
+    X, _ = synth.workload("hr_mlp_down", seed=0, device=DEV)
+    vals, meta, _ = rtl.sparsify_pack(X, comp=rtl.COMP_GROUP)
+    torch.cuda.synchronize()
+    ref = oracle.sparsify_pack_oracle(synth.bits(X), scope=oracle.GROUP)
+    assert np.array_equal(meta.cpu().numpy(), ref["meta"])
+    assert np.array_equal(synth.bits(vals), ref["vals"])
+
+
+def test_results_are_deterministic():
+    X, W = synth.workload("out_proj", seed=3, device=DEV)
+    a = rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP)
+    b = rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP)
+    assert torch.equal(a, b)
+
+
+def test_minimal_and_skinny_shapes():
+    for (M, N, K) in [(1, 7, 64), (7, 1, 64), (2, 2, 4096), (1000, 8, 64), (8, 1000, 128)]:
+        X = synth.activations("normal", M, K, seed=M + N, device=DEV)
+        W = synth.weights(N, K, seed=K, device=DEV, std=1.0)
+        ref = oracle.sparse_linear_oracle(synth.bits(X), synth.bits(W), scope=oracle.GROUP)
+        check_y(rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP), ref["Y"])
+        check_y(rtl.dense_linear(X, W), oracle.dense_linear_oracle(synth.bits(X), synth.bits(W)))
+
+
+def test_packed_linear_scales_and_canonical_operand():
+    """rtl_packed_linear on the canonical operand written by rtl_sparsify_pack, with the deferred
+    ROW / TENSOR factors, equals rtl_sparse_linear bit for bit."""
+    X, W = synth.workload("tiny", seed=4, device=DEV)
+    for comp in (rtl.COMP_ROW, rtl.COMP_TENSOR):
+        vals, meta, scale = rtl.sparsify_pack(X, comp=comp)
+        kw = dict(row_scale=scale) if comp == rtl.COMP_ROW else dict(tensor_scale=scale)
+        Yp = rtl.packed_linear(vals, meta, W, **kw)
+        assert torch.equal(Yp, rtl.sparse_linear(X, W, comp=comp))
+
+
+def test_denoising_step_sweep_two_blocks():
+    """Two of the 60 blocks of the full-step sweep (QKV, out-proj, fc1, fc2 at M = 4608), fresh
+    seeded tensors per layer: metadata in full, outputs on sampled rows."""
+    for block in range(2):
+        for kind in synth.SWEEP_LAYERS:
+            w = synth.WORKLOADS[kind]
+            seed = synth.layer_seed(block, kind)
+            X = synth.activations(w["x"], w["M"], w["K"], seed, DEV)
+            W = synth.weights(w["N"], w["K"], seed + 500, DEV)
+            vals, meta, _ = rtl.sparsify_pack(X, comp=rtl.COMP_GROUP)
+            Y = rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP)
+            Xb = synth.bits(X)
+            keep = oracle.topk24(Xb)
+            _, meta_ref = oracle.pack(Xb, keep)
+            assert np.array_equal(meta.cpu().numpy(), meta_ref)
+            rows = sampled_rows(w["M"], 6, seed)
+            sel = torch.from_numpy(rows).to(DEV)
+            ref = oracle.sparse_linear_oracle(Xb[rows], synth.bits(W), scope=oracle.GROUP)["Y"]
+            check_y(Y[sel], ref)
