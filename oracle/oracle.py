@@ -32,6 +32,9 @@ _lib.orc_apply.argtypes = [_p, _p, _p, _i64, _i64, _i64, C.c_int, C.c_int, _p, _
 _lib.orc_pack.argtypes = [_p, _i64, _p, _i64, _i64, _p, _p]
 _lib.orc_unpack.argtypes = [_p, _p, _i64, _i64, _p]
 _lib.orc_linear.argtypes = [_p, _p, _p, _i64, _i64, _i64, _i64, _i64, _i64, _p]
+_lib.orc_lora_delta.argtypes = [_p, _p, _i64, _i64, _i64, _p]
+_lib.orc_linear_f32w.argtypes = [_p, _p, _i64, _i64, _i64, _i64, _i64, _p]
+_lib.orc_add.argtypes = [_p, _p, _i64, _p]
 _lib.orc_widen.argtypes = [_p, _i64, _i64, _i64, _p]
 _lib.orc_round_bf16.argtypes = [_p, _i64, _p]
 _lib.orc_rfe.argtypes = [_p, _p, _i64]
@@ -170,3 +173,40 @@ def sparse_linear_oracle(X, W, bias=None, scope=GROUP, eps=1e-8, rows=None):
 def dense_linear_oracle(X, W, bias=None, rows=None):
     """Eq. (linear_layer): Y = X W^T (+ b), fp32 [M,N]."""
     return linear(bf16_to_f32(_u16(X)), W, bias, rows)
+
+
+def lora_delta(LA, LB):
+    """Eq. (sparse+lora): the LoRA product L_A L_B as fp32 [N,K]. L_A [N,R], L_B [R,K] bf16 bits."""
+    LA, LB = _u16(LA), _u16(LB)
+    N, R = LA.shape
+    K = LB.shape[1]
+    assert LB.shape[0] == R
+    D = np.empty((N, K), dtype=np.float32)
+    _lib.orc_lora_delta(_ptr(LA), _ptr(LB), N, K, R, _ptr(D))
+    return D
+
+
+def linear_f32w(A, Wf, rows=None):
+    """Y = A Wf^T with fp32 operands (fp32 triple loop, k ascending)."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    Wf = np.ascontiguousarray(Wf, dtype=np.float32)
+    M, K = A.shape
+    N = Wf.shape[0]
+    m0, m1 = (0, M) if rows is None else rows
+    Y = np.zeros((M, N), dtype=np.float32)
+    rc = _lib.orc_linear_f32w(_ptr(A), _ptr(Wf), M, N, K, m0, m1, _ptr(Y))
+    assert rc == 0
+    return Y
+
+
+def sparse_lora_linear_oracle(X, W, LA, LB, bias=None, scope=GROUP, eps=1e-8, delta=None):
+    """The whole of Alg. 1: Y = S(X) W^T (+ b) + X (L_A L_B)^T, fp32 [M,N].
+
+    `delta` lets a caller reuse the LoRA product L_A L_B across calls (it does not depend on X)."""
+    r = sparse_linear_oracle(X, W, bias, scope, eps)
+    D = lora_delta(LA, LB) if delta is None else delta
+    Yr = linear_f32w(bf16_to_f32(_u16(X)), D)
+    Y = np.empty_like(Yr)
+    _lib.orc_add(_ptr(r["Y"]), _ptr(Yr), Yr.size, _ptr(Y))
+    r["Y_s"], r["Y_r"], r["Y"] = r["Y"], Yr, Y
+    return r

@@ -12,6 +12,8 @@
  *                                          -> orc_linear   (fp32 triple loop on the masked input)
  *   Eq. (linear_layer) Y = X W^T           -> orc_linear on the un-masked input
  *   App. RFE metric                        -> orc_rfe
+ *   Eq. (sparse+lora), Alg. 1 "Y_r <- X (L_A L_B)^T", "Y <- Y_s + Y_r"
+ *                                          -> orc_lora_delta, orc_linear_f32w, orc_add
  *
  * Only tests, the smoke check and the benchmark's cpu_baseline leg may call this file.
  * It shares no code, tables or constants with the HIP library.
@@ -190,6 +192,41 @@ int orc_linear(const float* S, const uint16_t* W, const uint16_t* bias, int64_t 
             if (bias) acc = acc + bf16_to_f32(bias[n]);
             Y[m * N + n] = acc;
         }
+    return 0;
+}
+
+/* LoRA product of Eq. (sparse+lora): D[n,k] = sum_r L_A[n,r] * L_B[r,k], fp32, r ascending.
+ * L_A [N,R] and L_B [R,K] are bf16 bit patterns, row-major. */
+int orc_lora_delta(const uint16_t* LA, const uint16_t* LB, int64_t N, int64_t K, int64_t R, float* D) {
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            float acc = 0.0f;
+            for (int64_t r = 0; r < R; ++r)
+                acc = acc + bf16_to_f32(LA[n * R + r]) * bf16_to_f32(LB[r * K + k]);
+            D[n * K + k] = acc;
+        }
+    return 0;
+}
+
+/* Y[m,n] = sum_k A[m,k] * Wf[n,k] with an fp32 weight matrix (the LoRA product above), fp32,
+ * k ascending. Rows m in [m0, m1). */
+int orc_linear_f32w(const float* A, const float* Wf, int64_t M, int64_t N, int64_t K,
+                    int64_t m0, int64_t m1, float* Y) {
+    if (m0 < 0 || m1 > M || m0 > m1) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = m0; m < m1; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float acc = 0.0f;
+            for (int64_t k = 0; k < K; ++k) acc = acc + A[m * K + k] * Wf[n * K + k];
+            Y[m * N + n] = acc;
+        }
+    return 0;
+}
+
+/* out = a + b elementwise in fp32 (Alg. 1 "Y <- Y_s + Y_r"). */
+int orc_add(const float* a, const float* b, int64_t n, float* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = a[i] + b[i];
     return 0;
 }
 

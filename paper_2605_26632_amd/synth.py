@@ -102,3 +102,12 @@ def from_bits(a, device="cpu"):
     """numpy uint16 bit patterns -> bf16 tensor."""
     import numpy as np
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
+
+
+def lora(N, K, R, seed, device="cpu", std_a=0.02, std_b=0.02):
+    """LoRA factors L_A bf16 [N,R], L_B bf16 [R,K] ~ N(0, std). (The paper initialises trained
+    factors near zero; random factors of weight-like scale exercise the kernel harder.)"""
+    g = _gen(seed, device)
+    la = torch.randn((N, R), generator=g, device=device, dtype=torch.float32) * std_a
+    lb = torch.randn((R, K), generator=g, device=device, dtype=torch.float32) * std_b
+    return la.to(torch.bfloat16).contiguous(), lb.to(torch.bfloat16).contiguous()

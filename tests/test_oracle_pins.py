@@ -239,3 +239,44 @@ def test_rfe_definition_and_sanity_on_config_inputs():
     e_none = oracle.rfe(dense, oracle.sparse_linear_oracle(Xb, Wb, scope=oracle.NONE)["Y"])
     e_grp = oracle.rfe(dense, oracle.sparse_linear_oracle(Xb, Wb, scope=oracle.GROUP)["Y"])
     assert 0 < e_none < 0.6 and 0 < e_grp < 0.6   # an approximation, but not garbage
+
+
+# ---------------------------------------------------------------- LoRA branch (Eq. sparse+lora)
+def test_lora_branch_matches_fp64_and_is_low_rank():
+    X, W = synth.workload("tiny", seed=5, M=40)
+    LA, LB = synth.lora(W.shape[0], W.shape[1], 16, seed=6, std_a=1.0, std_b=1.0)
+    Xb, Wb, LAb, LBb = (synth.bits(t) for t in (X, W, LA, LB))
+    r = oracle.sparse_lora_linear_oracle(Xb, Wb, LAb, LBb, scope=oracle.GROUP)
+    Xf = oracle.bf16_to_f32(Xb).astype(np.float64)
+    A64 = oracle.bf16_to_f32(LAb).astype(np.float64)
+    B64 = oracle.bf16_to_f32(LBb).astype(np.float64)
+    ref_r = Xf @ (A64 @ B64).T
+    assert np.allclose(r["Y_r"], ref_r, rtol=0, atol=3e-5 * np.abs(ref_r).max())
+    # (X L_B^T) L_A^T is the same map: the order of the two small products does not matter
+    assert np.allclose((Xf @ B64.T) @ A64.T, ref_r, rtol=1e-9, atol=1e-9 * np.abs(ref_r).max())
+    assert np.linalg.matrix_rank(r["Y_r"].astype(np.float64), tol=1e-3 * np.abs(ref_r).max()) <= 16
+    # the sum is the sparse output plus the residual, nothing else
+    base = oracle.sparse_linear_oracle(Xb, Wb, scope=oracle.GROUP)["Y"]
+    assert np.array_equal(r["Y_s"], base)
+    assert np.allclose(r["Y"], base.astype(np.float64) + ref_r, rtol=0, atol=3e-5 * np.abs(ref_r).max())
+
+
+def test_lora_special_cases():
+    X, W = synth.workload("tiny", seed=7, M=24)
+    Xb, Wb = synth.bits(X), synth.bits(W)
+    N, K = W.shape
+    # zero L_A: the branch vanishes and Alg. 1 is the sparse linear alone
+    LA0 = np.zeros((N, 8), dtype=np.uint16)
+    LB = synth.bits(synth.lora(N, K, 8, seed=8)[1])
+    r0 = oracle.sparse_lora_linear_oracle(Xb, Wb, LA0, LB, scope=oracle.NONE)
+    assert np.array_equal(r0["Y"], oracle.sparse_linear_oracle(Xb, Wb, scope=oracle.NONE)["Y"])
+    # full-rank "LoRA" with L_B = I and L_A = W: the residual is the dense layer itself
+    eye = bf(np.eye(K, dtype=np.float32))
+    r1 = oracle.sparse_lora_linear_oracle(Xb, Wb, Wb, eye, scope=oracle.NONE)
+    dense = oracle.dense_linear_oracle(Xb, Wb)
+    assert np.allclose(r1["Y_r"], dense, rtol=0, atol=3e-5 * np.abs(dense).max())
+    # the residual uses the un-sparsified X: it differs from feeding the masked activation
+    keep = oracle.topk24(Xb)
+    Xs = np.where(keep > 0, Xb, 0).astype(np.uint16)
+    assert not np.allclose(oracle.linear_f32w(oracle.bf16_to_f32(Xs), oracle.lora_delta(Wb, eye)), dense,
+                           atol=1e-3 * np.abs(dense).max())
