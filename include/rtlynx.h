@@ -117,6 +117,27 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * rtl_sparse_lora_linear - the whole of Alg. 1 including its LoRA residual (Eq. sparse+lora):
+ *     Y = compensate(sparsify_2:4(X)) W^T + X (L_A L_B)^T (+ b).
+ * The residual is evaluated as (X L_B^T) L_A^T: a skinny product T = X L_B^T ([M,R], kept in the
+ * workspace as a bf16 hi/lo pair) and a rank-R update added to the sparse product's fp32 accumulators inside the
+ * GEMM kernel, so Y_r is never materialised (method section, "CUDA Kernel Optimization", second item).
+ *
+ *   LA [N,R] bf16, row stride ldla (>= R); LB [R,K] bf16, row stride ldlb (>= K); both 16-byte
+ *   aligned with ldla % 8 == 0 and ldlb % 8 == 0. R must be 64 (the paper's rank), else RTL_ERR_SHAPE.
+ *   The compensation factors of ROW / TENSOR scope multiply the sparse product only.
+ *   Everything else as for rtl_sparse_linear.
+ *   workspace  rtl_sparse_lora_linear_workspace(M, N, K, R, comp) bytes, 256-byte aligned.
+ * ------------------------------------------------------------------------------------------- */
+size_t rtl_sparse_lora_linear_workspace(int64_t M, int64_t N, int64_t K, int64_t R, rtl_comp comp);
+rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, const void* LB,
+                                  const void* bias, void* Y,
+                                  int64_t M, int64_t N, int64_t K, int64_t R,
+                                  int64_t ldx, int64_t ldw, int64_t ldla, int64_t ldlb, int64_t ldy,
+                                  rtl_comp comp, float eps,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * rtl_dense_linear - Eq. (linear_layer), Y = X W^T (+ b), on the dense matrix instructions.
  * The denominator of every speedup the paper reports ("GEMM" column of its kernel tables).
  * Same layouts and alignment rules as rtl_sparse_linear; K % 64 == 0.

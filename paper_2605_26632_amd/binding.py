@@ -17,6 +17,7 @@ COMP = {"none": COMP_NONE, "group": COMP_GROUP, "row": COMP_ROW, "tensor": COMP_
 
 SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linear_workspace",
            "rtl_packed_linear", "rtl_sparse_linear_workspace", "rtl_sparse_linear",
+           "rtl_sparse_lora_linear_workspace", "rtl_sparse_lora_linear",
            "rtl_dense_linear_workspace", "rtl_dense_linear", "rtl_status_str", "rtl_version"]
 
 _lib = None
@@ -49,6 +50,11 @@ def lib():
         L.rtl_sparse_linear_workspace.restype = sz
         L.rtl_sparse_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, fl, vp, sz, vp]
         L.rtl_sparse_linear.restype = ci
+        L.rtl_sparse_lora_linear_workspace.argtypes = [i64, i64, i64, i64, ci]
+        L.rtl_sparse_lora_linear_workspace.restype = sz
+        L.rtl_sparse_lora_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64,
+                                             i64, i64, ci, fl, vp, sz, vp]
+        L.rtl_sparse_lora_linear.restype = ci
         L.rtl_dense_linear_workspace.argtypes = [i64, i64, i64]
         L.rtl_dense_linear_workspace.restype = sz
         L.rtl_dense_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, sz, vp]
@@ -147,6 +153,26 @@ def sparse_linear(X, W, bias=None, comp=COMP_GROUP, eps=1e-8, out=None, ws=None)
     st = L.rtl_sparse_linear(_p(X), _p(W), _p(bias), _p(Y), M, N, K, X.stride(0), W.stride(0),
                              Y.stride(0), comp, eps, _p(ws), ws.numel(), _stream())
     _check(st, "rtl_sparse_linear")
+    return Y
+
+
+def sparse_lora_linear_workspace(M, N, K, R=64, comp=COMP_GROUP):
+    return int(lib().rtl_sparse_lora_linear_workspace(M, N, K, R, comp))
+
+
+def sparse_lora_linear(X, W, LA, LB, bias=None, comp=COMP_GROUP, eps=1e-8, out=None, ws=None):
+    """rtl_sparse_lora_linear: Y = compensate(sparsify_2:4(X)) W^T + X (L_A L_B)^T (+ bias)."""
+    _need_cuda(X, W, LA, LB)
+    M, K = X.shape
+    N, R = LA.shape
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if out is None else out
+    L = lib()
+    if ws is None:
+        ws = _ws(L.rtl_sparse_lora_linear_workspace(M, N, K, R, comp), X.device)
+    st = L.rtl_sparse_lora_linear(_p(X), _p(W), _p(LA), _p(LB), _p(bias), _p(Y), M, N, K, R,
+                                  X.stride(0), W.stride(0), LA.stride(0), LB.stride(0), Y.stride(0),
+                                  comp, eps, _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_sparse_lora_linear")
     return Y
 
 

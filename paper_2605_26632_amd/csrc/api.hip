@@ -159,6 +159,59 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
 
+// rtl_sparse_lora_linear workspace: [rtl_sparse_linear workspace | T as two bf16 planes [2][M,64] | fp32 partials]
+size_t rtl_sparse_lora_linear_workspace(int64_t M, int64_t N, int64_t K, int64_t R, rtl_comp comp) {
+    if (M <= 0 || N <= 0 || K <= 0 || R != rtl::kLoraRank || !comp_ok(comp)) return 0;
+    return sparse_ws(M, N, K, comp).total + round_up((size_t)M * rtl::kLoraRank * 4, 256) +
+           round_up(rtl::lora_down_partial_bytes(M, K), 256);
+}
+
+rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, const void* LB,
+                                  const void* bias, void* Y, int64_t M, int64_t N, int64_t K,
+                                  int64_t R, int64_t ldx, int64_t ldw, int64_t ldla, int64_t ldlb,
+                                  int64_t ldy, rtl_comp comp, float eps, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    if (R != rtl::kLoraRank || ldla < R || ldlb < K) return RTL_ERR_SHAPE;
+    rtl_status st = check_linear(X, W, Y, M, N, K, ldx, ldw, ldy, K);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (!LA || !LB) return RTL_ERR_NULL;
+    if (ldla % 8 != 0 || ldlb % 8 != 0 || !aligned(LA, 16) || !aligned(LB, 16) ||
+        (bias && !aligned(bias, 2)))
+        return RTL_ERR_ALIGN;
+    const SparseWs ws = sparse_ws(M, N, K, comp);
+    const size_t t_off = ws.total, p_off = t_off + round_up((size_t)M * rtl::kLoraRank * 4, 256);
+    const size_t need = p_off + round_up(rtl::lora_down_partial_bytes(M, K), 256);
+    if (!workspace || workspace_bytes < need) return RTL_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    float* scale = reinterpret_cast<float*>(base + ws.scale);
+    uint16_t* T = reinterpret_cast<uint16_t*>(base + t_off);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = rtl::launch_lora_down(static_cast<const uint16_t*>(X), ldx,
+                                         static_cast<const uint16_t*>(LB), ldlb, M, K,
+                                         reinterpret_cast<float*>(base + p_off), T, s);
+    if (e != hipSuccess) return RTL_ERR_HIP;
+    e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
+                                  reinterpret_cast<uint16_t*>(base + ws.vals), nullptr, base + ws.meta,
+                                  scale, reinterpret_cast<float*>(base + ws.pack), s);
+    if (e != hipSuccess) return RTL_ERR_HIP;
+    rtl::GemmArgs g{};
+    g.A = reinterpret_cast<const uint16_t*>(base + ws.vals);
+    g.meta = base + ws.meta;
+    g.W = static_cast<const uint16_t*>(W);
+    g.bias = static_cast<const uint16_t*>(bias);
+    g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
+    g.tensor_scale = comp == RTL_COMP_TENSOR ? scale : nullptr;
+    g.Y = static_cast<uint16_t*>(Y);
+    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
+    g.T = T;
+    g.LA = static_cast<const uint16_t*>(LA);
+    g.ldla = ldla;
+    e = rtl::launch_gemm(true, g, s);
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
 size_t rtl_dense_linear_workspace(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
     return rtl::gemm_workspace_bytes(false, M, N, K);

@@ -120,8 +120,11 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     pn = (t % per_group) / gsize;
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+// MODE 0: plain linear. MODE 1 (sparse only): LoRA tail, the accumulators also receive T L_A^T before
+// the epilogue. MODE 2: split contraction, grid.y K ranges, fp32 partial tiles instead of Y.
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
+    static_assert(MODE == 0 || (MODE == 1 && SPARSE) || (MODE == 2 && !SPARSE), "mode/operand combination");
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -147,7 +150,21 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     int pm, pn;
     tile_coords(blockIdx.x, tiles_m, tiles_n, pm, pn);
     const int64_t m0 = (int64_t)pm * BM, n0 = (int64_t)pn * BN;
-    const int KT = (int)(a.K / KSTAGE);
+    int KT = (int)(a.K / KSTAGE);
+    int kt_first = 0;                                  // first stage of this workgroup's K range
+    if constexpr (MODE == 2) {
+        const int per = (KT + a.splits - 1) / a.splits;
+        kt_first = (int)blockIdx.y * per;
+        KT = max(0, min(per, KT - kt_first));
+        if (KT <= 0) {   // cannot happen for the range counts the launcher picks; stay defined anyway
+            float* out = a.partials + (int64_t)blockIdx.y * a.M * a.N;
+            for (int e = tid; e < BM * BN; e += NW * 64) {
+                const int64_t row = m0 + e / BN, col = n0 + e % BN;
+                if (row < a.M && col < a.N) out[row * a.N + col] = 0.f;
+            }
+            return;
+        }
+    }
 
     // ---- global -> LDS: every lane owns fixed chunks; rows past the edge are clamped to the last
     //      valid row (their products only reach outputs that are never stored) -----------------
@@ -158,7 +175,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         int row, c;
         unswz4(p, row, c);
         const int64_t gr = min(m0 + row, a.M - 1);
-        pa[s] = a.A + gr * a.lda + c * 8;
+        pa[s] = a.A + gr * a.lda + c * 8 + (int64_t)kt_first * A_ELEMS;
     }
     const uint16_t* pb[B_PER_W];
 #pragma unroll
@@ -167,7 +184,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         int row, c;
         if constexpr (SPARSE) unswz8(p, row, c); else unswz4(p, row, c);
         const int64_t gr = min(n0 + row, a.N - 1);
-        pb[s] = a.W + gr * a.ldw + c * 8;
+        pb[s] = a.W + gr * a.ldw + c * 8 + (int64_t)kt_first * KSTAGE;
     }
     const uint8_t* pmeta = nullptr;
     if constexpr (SPARSE) {
@@ -305,7 +322,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
         constexpr bool READ = decltype(read_tag)::value;
         static_assert(TM * TN <= 16 && HI - LO <= TM * TN, "unrolled by hand up to 16 matrix instructions");
-        static_assert(3 * TM + 2 * TN <= 2 * TM * TN + 2, "two reads per matrix instruction must cover a fragment set");
+        static_assert((SPARSE ? 2 * TM + 2 * TN : TM + TN) <= 2 * TM * TN + 2, "two reads per matrix instruction must cover a fragment set");
 #define RTL_MMA_STEP(N)                                                                       \
         mma_one(f, ix, sub_tag, std::integral_constant<int, N>{});                            \
         if constexpr (N < TM * TN) {                                                          \
@@ -400,11 +417,95 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     if (kt == KT - 2) { stage_step(kt, F{}, F{}, T{}, std::integral_constant<int, 0>{}); ++kt; }
     stage_step(kt, F{}, F{}, F{}, std::integral_constant<int, 0>{});
 
-    // ---- epilogue: optional fp32 scales, bias, bf16 RNE, store --------------------------------
     const float ts = a.tensor_scale ? a.tensor_scale[0] : 1.0f;
+
+    if constexpr (MODE == 2) {
+        // ---- split contraction: fp32 partial tile of this K range, no epilogue arithmetic ----
+        float* out = a.partials + (int64_t)blockIdx.y * a.M * a.N;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = n0 + wn * WTN + j * 32 + li;
+            if (col >= a.N) continue;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = m0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
+                    if (row < a.M) out[row * a.N + col] = acc[i][j][r];
+                }
+        }
+        return;
+    }
+
+    if constexpr (MODE == 1) {
+        // ---- LoRA tail (Alg. 1: Y <- Y_s + Y_r, accumulated on chip) --------------------------
+        // The ROW / TENSOR factors belong to the sparse product only, so they are applied to the
+        // accumulators first. Then Y_r = T L_A^T, T = X L_B^T (bf16 [M,64]), is added by four dense
+        // matrix-instruction steps over the rank; SMFMAC and MFMA 32x32 share one accumulator layout.
+        if (a.row_scale || a.tensor_scale) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = min(m0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * kb + (r % 4), a.M - 1);
+                    const float f = (a.row_scale ? a.row_scale[row] : 1.0f) * ts;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j][r] *= f;
+                }
+        }
+        wait_vmcnt_lgkm0<0>();
+        __builtin_amdgcn_s_barrier();          // the ring is free: reuse it for the two rank tiles
+        constexpr int T_LOADS = BM * 128 / 1024, LA_LOADS = BN * 128 / 1024;   // rows of 64 bf16
+        static_assert(T_LOADS % NW == 0 && LA_LOADS % NW == 0, "rank tiles must divide over the waves");
+        static_assert((2 * BM + BN) * 128 <= L::kTotal, "rank tiles fit in the ring");
+        const int64_t plane = a.M * kLoraRank;          // T is two bf16 planes: hi, lo
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int s = 0; s < T_LOADS / NW; ++s) {
+                const int p = (wave * (T_LOADS / NW) + s) * 64 + lane;
+                int row, c;
+                unswz8(p, row, c);
+                lds_dma16(a.T + h * plane + min(m0 + row, a.M - 1) * kLoraRank + c * 8,
+                          lds0 + h * BM * 128 + (wave * (T_LOADS / NW) + s) * 1024);
+            }
+#pragma unroll
+        for (int s = 0; s < LA_LOADS / NW; ++s) {
+            const int p = (wave * (LA_LOADS / NW) + s) * 64 + lane;
+            int row, c;
+            unswz8(p, row, c);
+            lds_dma16(a.LA + min(n0 + row, a.N - 1) * a.ldla + c * 8,
+                      lds0 + 2 * BM * 128 + (wave * (LA_LOADS / NW) + s) * 1024);
+        }
+        wait_vmcnt_lgkm0<0>();
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int sub = 0; sub < kLoraRank / 16; ++sub) {
+            Frag8 th[TM], tl[TM], lb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                th[i].u = *reinterpret_cast<const uint4*>(smem + swz8(arow0 + i * 32, 2 * sub + kb));
+                tl[i].u = *reinterpret_cast<const uint4*>(smem + BM * 128 + swz8(arow0 + i * 32, 2 * sub + kb));
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                lb[j].u = *reinterpret_cast<const uint4*>(smem + 2 * BM * 128 + swz8(brow0 + j * 32, 2 * sub + kb));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tl[i].v, lb[j].v, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(th[i].v, lb[j].v, acc[i][j], 0, 0, 0);
+                }
+        }
+    }
+
+    // ---- epilogue: optional fp32 scales, bias, bf16 RNE, store --------------------------------
     auto finish = [&](float v, int64_t row, float bv) {
-        if (a.row_scale) v *= a.row_scale[row];
-        if (a.tensor_scale) v *= ts;
+        if constexpr (MODE != 1) {
+            if (a.row_scale) v *= a.row_scale[row];
+            if (a.tensor_scale) v *= ts;
+        }
         if (a.bias) v += bv;
         return (uint16_t)f32_to_bf16_rne(v);
     };
@@ -472,10 +573,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     }
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N>;
-    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES>;
+    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE>;
     static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -484,8 +585,23 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
         attr_set = true;
     }
     const int64_t tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(WAVES_M * WAVES_N * 64), L::kTotal, stream, a);
+    const dim3 grid((unsigned)tiles, MODE == 2 ? (unsigned)a.splits : 1u);
+    hipLaunchKernelGGL(kern, grid, dim3(WAVES_M * WAVES_N * 64), L::kTotal, stream, a);
     return hipGetLastError();
+}
+
+// T[m, r] = sum over the K ranges, in range order, of the fp32 partials, stored as two bf16 planes
+// hi = bf16(T), lo = bf16(T - hi): the matrix unit takes bf16 operands, and the pair keeps 16
+// significant bits so the residual is as accurate as the fp32-accumulated sparse product.
+__global__ __launch_bounds__(256) void lora_reduce_kernel(const float* __restrict__ partials, int splits,
+                                                          int64_t n, uint16_t* __restrict__ T) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float acc = 0.f;
+    for (int s = 0; s < splits; ++s) acc += partials[(int64_t)s * n + i];
+    const uint32_t hi = f32_to_bf16_rne(acc);
+    T[i] = (uint16_t)hi;
+    T[n + i] = (uint16_t)f32_to_bf16_rne(acc - __uint_as_float(hi << 16));
 }
 
 }  // namespace
@@ -506,10 +622,45 @@ static bool prefer_192(int64_t M, int64_t N) {
 
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
     if (sparse) {
-        if (prefer_192(a.M, a.N)) return launch_cfg<true, 256, 192, 4, 2, 3>(a, stream);
+        const bool lora = a.T != nullptr;
+        if (prefer_192(a.M, a.N)) {
+            if (lora) return launch_cfg<true, 256, 192, 4, 2, 3, 1>(a, stream);
+            return launch_cfg<true, 256, 192, 4, 2, 3>(a, stream);
+        }
+        if (lora) return launch_cfg<true, 256, 256, 2, 4, 3, 1>(a, stream);
         return launch_cfg<true, 256, 256, 2, 4, 3>(a, stream);
     }
     return launch_cfg<false, 256, 256, 2, 4, 3>(a, stream);
+}
+
+// ---- LoRA down-projection: a skinny product (N = 64) bound by reading X once. 128-row tiles times
+// enough K ranges to occupy every CU; the ranges are summed in a fixed order by a second kernel.
+static int lora_ranges(int64_t M, int64_t K, int* per_out) {
+    const int64_t tiles = (M + 127) / 128;
+    const int KT = (int)(K / 32);
+    int want = (int)((256 + tiles - 1) / tiles);
+    want = want < 1 ? 1 : (want > 16 ? 16 : want);
+    if (want > KT) want = KT;
+    const int per = (KT + want - 1) / want;
+    if (per_out) *per_out = per;
+    return (KT + per - 1) / per;           // every range holds at least one stage
+}
+int lora_down_splits(int64_t M, int64_t K) { return lora_ranges(M, K, nullptr); }
+size_t lora_down_partial_bytes(int64_t M, int64_t K) {
+    return (size_t)lora_down_splits(M, K) * (size_t)M * kLoraRank * sizeof(float);
+}
+hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
+                            int64_t K, float* partials, uint16_t* T, hipStream_t stream) {
+    GemmArgs g{};
+    g.A = X; g.W = LB; g.partials = partials;
+    g.M = M; g.N = kLoraRank; g.K = K; g.lda = ldx; g.ldw = ldlb; g.ldy = kLoraRank;
+    g.splits = lora_down_splits(M, K);
+    hipError_t e = launch_cfg<false, 128, 64, 4, 1, 4, 2>(g, stream);
+    if (e != hipSuccess) return e;
+    const int64_t n = M * kLoraRank;
+    hipLaunchKernelGGL(lora_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                       partials, g.splits, n, T);
+    return hipGetLastError();
 }
 
 }  // namespace rtl

@@ -36,10 +36,23 @@ struct GemmArgs {
     const float* row_scale; // nullable [M]
     const float* tensor_scale; // nullable [1]
     uint16_t* Y;            // [M,N] (ldy)
-    float* partials;        // workspace for split contraction (may be null when unused)
+    float* partials;        // split contraction: fp32 partial results [splits][M][N]
     int64_t M, N, K, lda, ldw, ldy;
+    // LoRA tail of the sparse kernel (Alg. 1 "Y_r <- X (L_A L_B)^T" as (X L_B^T) L_A^T):
+    const uint16_t* T;      // nullable: X L_B^T as two bf16 planes (hi, lo), [2][M,64]
+    const uint16_t* LA;     // L_A bf16 [N,64] (ldla)
+    int64_t ldla;
+    int splits;             // split contraction: number of K ranges (grid.y)
 };
 size_t gemm_workspace_bytes(bool sparse, int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream);
+
+// LoRA down-projection T = X L_B^T ([2][M,64] bf16 hi/lo planes): split-K partial products +
+// ordered reduction.
+constexpr int kLoraRank = 64;
+int lora_down_splits(int64_t M, int64_t K);
+size_t lora_down_partial_bytes(int64_t M, int64_t K);
+hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
+                            int64_t K, float* partials, uint16_t* T, hipStream_t stream);
 
 }  // namespace rtl

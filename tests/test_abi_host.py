@@ -76,5 +76,14 @@ def test_linear_entry_points_reject_bad_arguments():
     def packed(vals=FAKE, meta=FAKE, W=FAKE, Y=FAKE, M=4, N=4, K=64, ldw=64, ldy=4):
         return L.rtl_packed_linear(vals, meta, None, None, W, None, Y, M, N, K, ldw, ldy, FAKE, 1 << 30, None)
 
+    def lora(LA=FAKE, LB=FAKE, R=64, ldla=64, ldlb=64, ws=FAKE, wsb=1 << 30, K=64):
+        return L.rtl_sparse_lora_linear(FAKE, FAKE, LA, LB, None, FAKE, 4, 4, K, R, K, K, ldla, ldlb, 4, 1, 1e-8,
+                                        ws, wsb, None)
+
+    assert lora(R=32) == 2 and lora(R=128) == 2 and lora(ldla=32) == 2 and lora(ldlb=32) == 2
+    assert lora(LA=None) == 1 and lora(LB=None) == 1 and lora(LA=FAKE + 8) == 3 and lora(wsb=64) == 4
+    assert L.rtl_sparse_lora_linear_workspace(4096, 3072, 12288, 64, 1) > L.rtl_sparse_linear_workspace(4096, 3072, 12288, 1)
+    assert L.rtl_sparse_lora_linear_workspace(4096, 3072, 12288, 32, 1) == 0
+
     assert packed(meta=None) == 1 and packed(vals=None) == 1 and packed(K=96) == 2
     assert packed(meta=FAKE + 4) == 3 and packed(M=0) == 0

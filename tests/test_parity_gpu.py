@@ -261,3 +261,48 @@ def test_denoising_step_sweep_two_blocks():
             sel = torch.from_numpy(rows).to(DEV)
             ref = oracle.sparse_linear_oracle(Xb[rows], synth.bits(W), scope=oracle.GROUP)["Y"]
             check_y(Y[sel], ref)
+
+
+# ------------------------------------------------------------------ LoRA residual (whole Alg. 1)
+@pytest.mark.parametrize("comp", COMPS)
+def test_sparse_lora_linear_tiny_config(comp):
+    X, W = synth.workload("tiny", seed=0, device=DEV)
+    LA, LB = synth.lora(W.shape[0], W.shape[1], 64, seed=31, device=DEV, std_a=0.05, std_b=0.05)
+    Y = rtl.sparse_lora_linear(X, W, LA, LB, comp=comp)
+    ref = oracle.sparse_lora_linear_oracle(synth.bits(X), synth.bits(W), synth.bits(LA), synth.bits(LB), scope=comp)
+    check_y(Y, ref["Y"])
+    # the residual matters at this scale: leaving it out must break the tolerance
+    assert rel_max_err(ref["Y_s"], ref["Y"]) > 5 * Y_TOL
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 200, 128), (1, 1, 64), (129, 257, 192), (257, 513, 320)])
+def test_sparse_lora_linear_ragged(M, N, K):
+    X = synth.activations("laplace_outlier", M, K, seed=41, device=DEV)
+    W = synth.weights(N, K, seed=42, device=DEV, std=1.0)
+    b = synth.bias(N, seed=43, device=DEV, std=2.0)
+    LA, LB = synth.lora(N, K, 64, seed=44, device=DEV, std_a=0.5, std_b=0.5)
+    Y = rtl.sparse_lora_linear(X, W, LA, LB, bias=b, comp=rtl.COMP_ROW)
+    ref = oracle.sparse_lora_linear_oracle(synth.bits(X), synth.bits(W), synth.bits(LA), synth.bits(LB),
+                                           bias=synth.bits(b), scope=oracle.ROW)
+    check_y(Y, ref["Y"])
+
+
+def test_sparse_lora_linear_zero_factor_equals_sparse_linear():
+    X, W = synth.workload("out_proj", seed=5, device=DEV)
+    LA, LB = synth.lora(W.shape[0], W.shape[1], 64, seed=6, device=DEV)
+    Y0 = rtl.sparse_lora_linear(X, W, torch.zeros_like(LA), LB, comp=rtl.COMP_GROUP)
+    assert torch.equal(Y0, rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP))
+
+
+@pytest.mark.parametrize("name", ["mlp_down", "fc1"])
+def test_sparse_lora_linear_full_size_sampled_rows(name):
+    X, W = synth.workload(name, seed=0, device=DEV)
+    M, K = X.shape
+    N = W.shape[0]
+    LA, LB = synth.lora(N, K, 64, seed=77, device=DEV)
+    Y = rtl.sparse_lora_linear(X, W, LA, LB, comp=rtl.COMP_GROUP)
+    rows = sampled_rows(M, 12, seed=5)
+    sel = torch.from_numpy(rows).to(DEV)
+    ref = oracle.sparse_lora_linear_oracle(synth.bits(X[sel]), synth.bits(W), synth.bits(LA), synth.bits(LB),
+                                           scope=oracle.GROUP)
+    check_y(Y[sel], ref["Y"])
