@@ -63,6 +63,22 @@ __device__ __forceinline__ void lds_dma4(const void* gaddr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
                  :: "s"(lds_base), "v"(gaddr) : "memory");
 }
+// Same with a wave-uniform 64-bit base (SGPR pair) plus a 32-bit per-lane byte offset: the per-lane
+// state of a stream shrinks to one register and the walk along K is a scalar addition.
+__device__ __forceinline__ uint64_t uniform64(const void* p) {   // pin a wave-uniform pointer to SGPRs
+    const uint64_t b = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ void lds_dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_base), "v"(voff), "s"(uniform64(sbase)) : "memory");
+}
+__device__ __forceinline__ void lds_dma4_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(lds_base), "v"(voff), "s"(uniform64(sbase)) : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_lgkm0() {   // vmcnt <= N, all LDS reads returned
     __builtin_amdgcn_s_waitcnt(0x0070 | (N & 0xF) | ((N >> 4) << 14));
@@ -168,29 +184,35 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
 
     // ---- global -> LDS: every lane owns fixed chunks; rows past the edge are clamped to the last
     //      valid row (their products only reach outputs that are never stored) -----------------
-    const uint16_t* pa[A_PER_W];
+    // wave-uniform bases of this tile's three streams, already advanced to the first stage
+    const uint8_t* base_a = reinterpret_cast<const uint8_t*>(a.A + m0 * a.lda + (int64_t)kt_first * A_ELEMS);
+    const uint8_t* base_b = reinterpret_cast<const uint8_t*>(a.W + n0 * a.ldw + (int64_t)kt_first * KSTAGE);
+    const int64_t rows_a = a.M - m0, rows_b = a.N - n0;     // valid rows from the tile's first row
+    uint32_t oa[A_PER_W];
 #pragma unroll
     for (int s = 0; s < A_PER_W; ++s) {
         const int p = (wave * A_PER_W + s) * 64 + lane;
         int row, c;
         unswz4(p, row, c);
-        const int64_t gr = min(m0 + row, a.M - 1);
-        pa[s] = a.A + gr * a.lda + c * 8 + (int64_t)kt_first * A_ELEMS;
+        const int64_t gr = min((int64_t)row, rows_a - 1);
+        oa[s] = (uint32_t)(gr * a.lda * 2 + c * 16);
     }
-    const uint16_t* pb[B_PER_W];
+    uint32_t ob[B_PER_W];
 #pragma unroll
     for (int s = 0; s < B_PER_W; ++s) {
         const int p = (wave * B_PER_W + s) * 64 + lane;
         int row, c;
         if constexpr (SPARSE) unswz8(p, row, c); else unswz4(p, row, c);
-        const int64_t gr = min(n0 + row, a.N - 1);
-        pb[s] = a.W + gr * a.ldw + c * 8 + (int64_t)kt_first * KSTAGE;
+        const int64_t gr = min((int64_t)row, rows_b - 1);
+        ob[s] = (uint32_t)(gr * a.ldw * 2 + c * 16);
     }
-    const uint8_t* pmeta = nullptr;
+    const uint8_t* base_m = nullptr;
+    uint32_t om = 0;
     if constexpr (SPARSE) {
         // k-major records: the 256 rows of this tile are one contiguous 2 KiB run per stage and
         // wave w moves its 256-byte share (rows 32 w .. 32 w + 31), 4 bytes per lane
-        pmeta = a.meta + (m0 + wave * (32 * M_PER_W)) * 8 + lane * 4;
+        base_m = a.meta + m0 * 8;
+        om = (uint32_t)(wave * (32 * M_PER_W) * 8 + lane * 4);
     }
 
     const int64_t meta_stride = ((a.M + 255) / 256 * 256) * 8;   // bytes between 64-k blocks
@@ -202,15 +224,15 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         constexpr int n = decltype(n_tag)::value;
         const uint32_t base = lds0 + stage * L::kStage;
         if constexpr (n < A_PER_W) {
-            lds_dma16(pa[n] + (int64_t)kt * A_ELEMS, base + (wave * A_PER_W + n) * 1024);
+            lds_dma16_so(base_a + (int64_t)kt * (A_ELEMS * 2), oa[n], base + (wave * A_PER_W + n) * 1024);
         } else if constexpr (n < A_PER_W + B_PER_W) {
             constexpr int s = n - A_PER_W;
-            lds_dma16(pb[s] + (int64_t)kt * KSTAGE,
-                      base + L::kABytes + L::kMetaBytes + (wave * B_PER_W + s) * 1024);
+            lds_dma16_so(base_b + (int64_t)kt * (KSTAGE * 2), ob[s],
+                         base + L::kABytes + L::kMetaBytes + (wave * B_PER_W + s) * 1024);
         } else if constexpr (SPARSE && n < A_PER_W + B_PER_W + M_PER_W) {
             constexpr int s = n - A_PER_W - B_PER_W;
-            lds_dma4(pmeta + (int64_t)kt * meta_stride + s * 256,
-                     base + L::kABytes + (wave * M_PER_W + s) * 256);
+            lds_dma4_so(base_m + (int64_t)kt * meta_stride + s * 256, om,
+                        base + L::kABytes + (wave * M_PER_W + s) * 256);
         }
     };
     auto gload = [&](int kt, int stage) {
