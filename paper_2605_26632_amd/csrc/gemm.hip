@@ -540,19 +540,46 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         wait_vmcnt_lgkm0<0>();
         __builtin_amdgcn_s_barrier();     // every wave is done reading the ring
         uint8_t* ep = smem + wave * (WTM * ROWB);
+        // Two accumulator registers (rows r, r + 1 of one column) are converted by one packed
+        // fp32 -> bf16 instruction (round to nearest even) and leave as two 16-bit LDS writes. The
+        // plain case (no factors, no bias) is kept free of any other per-element work: with 128
+        // elements per lane the epilogue is otherwise bound by its vector ALU work, not by stores.
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        auto put2 = [&](float v0, float v1, int rl, int cl) {
+            const f32x2 pv = {v0, v1};
+            const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, bf16x2));
+            *reinterpret_cast<uint16_t*>(ep + rl * ROWB + cl * 2) = (uint16_t)pk;
+            *reinterpret_cast<uint16_t*>(ep + (rl + 1) * ROWB + cl * 2) = (uint16_t)(pk >> 16);
+        };
+        const bool scaled = MODE != 1 && (a.row_scale || a.tensor_scale);
+        if (!scaled && !a.bias) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = min(n0 + wn * WTN + j * 32 + li, a.N - 1);
-            const float bv = a.bias ? __uint_as_float((uint32_t)a.bias[col] << 16) : 0.f;
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int rl = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
-                    const int64_t row = min(m0 + wm * WTM + rl, a.M - 1);
-                    *reinterpret_cast<uint16_t*>(ep + rl * ROWB + (j * 32 + li) * 2) =
-                        finish(acc[i][j][r], row, bv);
-                }
+                    for (int r = 0; r < 16; r += 2)
+                        put2(acc[i][j][r], acc[i][j][r + 1], i * 32 + 8 * (r / 4) + 4 * kb + (r % 4), j * 32 + li);
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = min(n0 + wn * WTN + j * 32 + li, a.N - 1);
+                const float bv = a.bias ? __uint_as_float((uint32_t)a.bias[col] << 16) : 0.f;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        const int rl = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
+                        float f0 = 1.0f, f1 = 1.0f;
+                        if (scaled) {
+                            const int64_t row = min(m0 + wm * WTM + rl, a.M - 1);
+                            f0 = (a.row_scale ? a.row_scale[row] : 1.0f) * ts;
+                            f1 = (a.row_scale ? a.row_scale[min(row + 1, a.M - 1)] : 1.0f) * ts;
+                        }
+                        put2(acc[i][j][r] * f0 + bv, acc[i][j][r + 1] * f1 + bv, rl, j * 32 + li);
+                    }
+            }
         }
         // same wave reads back what it wrote: LDS operations of a wave complete in order
         constexpr int CPR = WTN / 8;               // 16-byte chunks per tile row
