@@ -546,11 +546,21 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         // elements per lane the epilogue is otherwise bound by its vector ALU work, not by stores.
         typedef float f32x2 __attribute__((ext_vector_type(2)));
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        // A lane holds rows rl, rl + 1 of ONE column; its neighbour (lane ^ 1) holds the same rows
+        // of the next column. The pair swaps halves (one DPP move, one byte permute) so that the
+        // even lane owns row rl and the odd lane row rl + 1 of BOTH columns: one 32-bit LDS write
+        // per lane instead of two 16-bit ones.
+        const bool odd = lane & 1;
+        const uint32_t sel = odd ? 0x03020706u : 0x05040100u;   // v_perm_b32: bytes 0-3 = own, 4-7 = partner
+        const int rsel = odd ? ROWB : 0;                        // odd lanes write the row below
         auto put2 = [&](float v0, float v1, int rl, int cl) {
             const f32x2 pv = {v0, v1};
-            const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, bf16x2));
-            *reinterpret_cast<uint16_t*>(ep + rl * ROWB + cl * 2) = (uint16_t)pk;
-            *reinterpret_cast<uint16_t*>(ep + (rl + 1) * ROWB + cl * 2) = (uint16_t)(pk >> 16);
+            const uint32_t own = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, bf16x2));
+            const uint32_t partner = (uint32_t)__builtin_amdgcn_mov_dpp((int)own, 0xB1, 0xF, 0xF, true);
+            // even: (own.lo, partner.lo) = row rl, columns (cl, cl + 1)
+            // odd : (partner.hi, own.hi) = row rl + 1, columns (cl - 1, cl)
+            const uint32_t w = __builtin_amdgcn_perm(partner, own, sel);
+            *reinterpret_cast<uint32_t*>(ep + rl * ROWB + rsel + (cl & ~1) * 2) = w;
         };
         const bool scaled = MODE != 1 && (a.row_scale || a.tensor_scale);
         if (!scaled && !a.bias) {
