@@ -22,6 +22,12 @@ WORKLOADS = {
     "hr_fc1": dict(M=16896, K=3072, N=12288, x="laplace"),
     "hr_qkv": dict(M=16896, K=3072, N=9216, x="laplace"),
     "hr_out_proj": dict(M=16896, K=3072, N=3072, x="laplace"),
+    # other models of the paper's appendix (layer-shape tables of FLUX.1-dev and Z-Image), 4096 image tokens
+    "flux_single_in": dict(M=4096, K=3072, N=21504, x="laplace"),     # single-stream fused QKV + MLP-up
+    "flux_single_out": dict(M=4096, K=15360, N=3072, x="gelu"),       # single-stream fused out + MLP-down
+    "zimage_up": dict(M=4096, K=3840, N=10240, x="laplace"),
+    "zimage_down": dict(M=4096, K=10240, N=3840, x="gelu"),
+    "zimage_attn": dict(M=4096, K=3840, N=3840, x="laplace"),
 }
 SWEEP_BLOCKS = 60
 SWEEP_LAYERS = ("qkv", "out_proj", "fc1", "fc2")

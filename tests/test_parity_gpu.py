@@ -306,3 +306,16 @@ def test_sparse_lora_linear_full_size_sampled_rows(name):
     ref = oracle.sparse_lora_linear_oracle(synth.bits(X[sel]), synth.bits(W), synth.bits(LA), synth.bits(LB),
                                            scope=oracle.GROUP)
     check_y(Y[sel], ref["Y"])
+
+
+@pytest.mark.parametrize("name", ["flux_single_in", "flux_single_out", "zimage_up", "zimage_down", "zimage_attn"])
+def test_other_model_layer_shapes(name):
+    """Layer shapes of the other two models in the paper's appendix tables (FLUX.1-dev single-stream,
+    Z-Image), sampled rows against the oracle."""
+    X, W = synth.workload(name, seed=2, device=DEV)
+    M = X.shape[0]
+    Y = rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP)
+    rows = sampled_rows(M, 8, seed=11)
+    sel = torch.from_numpy(rows).to(DEV)
+    ref = oracle.sparse_linear_oracle(synth.bits(X[sel]), synth.bits(W), scope=oracle.GROUP)["Y"]
+    check_y(Y[sel], ref)
