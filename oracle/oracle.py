@@ -44,6 +44,10 @@ _lib.orc_bf16_to_f32.restype = C.c_float
 _lib.orc_f32_to_bf16.argtypes = [C.c_float]
 _lib.orc_f32_to_bf16.restype = C.c_uint16
 _lib.orc_num_threads.restype = C.c_int
+_lib.orc_e4m3_encode.argtypes = [_p, _i64, _p]
+_lib.orc_e4m3_decode.argtypes = [_p, _i64, _p]
+_lib.orc_apply_fp8.argtypes = [_p, _p, _p, _i64, _i64, _i64, C.c_int, C.c_float, _p]
+_lib.orc_pack8.argtypes = [_p, _p, _i64, _i64, _p, _p]
 
 
 def num_threads() -> int:
@@ -209,4 +213,66 @@ def sparse_lora_linear_oracle(X, W, LA, LB, bias=None, scope=GROUP, eps=1e-8, de
     Y = np.empty_like(Yr)
     _lib.orc_add(_ptr(r["Y"]), _ptr(Yr), Yr.size, _ptr(Y))
     r["Y_s"], r["Y_r"], r["Y"] = r["Y"], Yr, Y
+    return r
+
+
+# ---- FP8 (E4M3) composition: implementation details, "orthogonal validation with FP8 quantization" ----
+
+def e4m3_encode(x):
+    """fp32 -> E4M3 codes (uint8), round-to-nearest-even, saturating at +-448, NaN -> 0x7F."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint8)
+    _lib.orc_e4m3_encode(_ptr(x), x.size, _ptr(out))
+    return out
+
+
+def e4m3_decode(c):
+    """E4M3 codes (uint8) -> fp32."""
+    c = np.ascontiguousarray(c, dtype=np.uint8)
+    out = np.empty(c.shape, dtype=np.float32)
+    _lib.orc_e4m3_decode(_ptr(c), c.size, _ptr(out))
+    return out
+
+
+def quantize_weights_fp8(W):
+    """Weights "directly quantized to FP8": the E4M3 code of every bf16 weight, no scale."""
+    return e4m3_encode(bf16_to_f32(_u16(W)))
+
+
+def sparsify_pack_fp8_oracle(X, x_scale, scope=GROUP, eps=1e-8):
+    """Alg. 1 up to the compressed operand with FP8 kept values.
+
+    Selection and the compensation factor are those of the bf16 path (they look at the bf16
+    input); the kept value is then (s * x) / x_scale quantised once to E4M3.
+    Returns dict(keep, s, Q (dense masked codes), vals (codes [M,K/2]), meta)."""
+    X = _u16(X)
+    M, K = X.shape
+    keep = topk24(X)
+    s = scales(X, keep, scope, eps)
+    Q = np.empty((M, K), dtype=np.uint8)
+    _lib.orc_apply_fp8(_ptr(X), _ptr(keep), _ptr(s), M, K, K, scope, float(np.float32(x_scale)), _ptr(Q))
+    vals = np.empty((M, K // 2), dtype=np.uint8)
+    meta = np.empty((M, K // 8), dtype=np.uint8)
+    rc = _lib.orc_pack8(_ptr(Q), _ptr(keep), M, K, _ptr(vals), _ptr(meta))
+    assert rc == 0
+    return dict(keep=keep, s=s, Q=Q, vals=vals, meta=meta)
+
+
+def sparse_linear_fp8_oracle(X, Wq, x_scale, bias=None, scope=GROUP, eps=1e-8, rows=None):
+    """W8A8 + 2:4 activation sparsity: Y = f * (Q Wq^T) (+ b), fp32 [M,N], with Q the quantised S(X),
+    Wq the E4M3 weight codes and f = x_scale (times the ROW / TENSOR compensation factor)."""
+    r = sparsify_pack_fp8_oracle(X, x_scale, scope, eps)
+    acc = linear_f32w(e4m3_decode(r["Q"]), e4m3_decode(Wq), rows)
+    f = np.float32(x_scale)
+    if scope == ROW:
+        f = (f * r["s"].astype(np.float32))[:, None]
+    elif scope == TENSOR:
+        f = f * np.float32(r["s"][0])
+    Y = (np.float32(1) * f * acc).astype(np.float32)
+    if bias is not None:
+        Y = Y + bf16_to_f32(_u16(bias))[None, :]
+        if rows is not None:
+            Y[: rows[0]] = 0
+            Y[rows[1]:] = 0
+    r["Y"] = Y.astype(np.float32)
     return r

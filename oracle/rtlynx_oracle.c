@@ -14,6 +14,10 @@
  *   App. RFE metric                        -> orc_rfe
  *   Eq. (sparse+lora), Alg. 1 "Y_r <- X (L_A L_B)^T", "Y <- Y_s + Y_r"
  *                                          -> orc_lora_delta, orc_linear_f32w, orc_add
+ *   Implementation details, "orthogonal validation with FP8 quantization" (symmetric FP8
+ *     quantisation of the activations, weights cast directly to FP8) on the 2:4 FP8 format of
+ *     the App. A table of sparse-tensor-core formats
+ *                                          -> orc_e4m3_encode / _decode, orc_apply_fp8, orc_pack8
  *
  * Only tests, the smoke check and the benchmark's cpu_baseline leg may call this file.
  * It shares no code, tables or constants with the HIP library.
@@ -27,6 +31,11 @@
  *  - GROUP arithmetic is fp32 in a fixed order (the order is part of the definition because
  *    the result is re-rounded to bf16 for the matrix unit); ROW/TENSOR norms are summed in fp64.
  *  - eps = 1e-8 sits inside the square root, added to the kept norm.
+ *  - FP8 is the 8-bit E4M3 format without infinities (bias 7, largest finite 448, S.1111.111 =
+ *    NaN); conversion is round-to-nearest-even and saturating: |v| >= 448 and +-inf give +-448,
+ *    NaN gives 0x7F. Weights are cast as they are; activations are divided by one caller-supplied
+ *    positive scale ("symmetric": no zero point) after selection and compensation, so every
+ *    kept value is rounded once: q = e4m3((s * x) * (1 / x_scale)), both products in fp32.
  */
 #include <stdint.h>
 #include <string.h>
@@ -227,6 +236,89 @@ int orc_linear_f32w(const float* A, const float* Wf, int64_t M, int64_t N, int64
 /* out = a + b elementwise in fp32 (Alg. 1 "Y <- Y_s + Y_r"). */
 int orc_add(const float* a, const float* b, int64_t n, float* out) {
     for (int64_t i = 0; i < n; ++i) out[i] = a[i] + b[i];
+    return 0;
+}
+
+/* ---- FP8 (E4M3, finite-only variant) ------------------------------------------------------ */
+
+/* Value of an E4M3 code: S.EEEE.MMM, bias 7; E = 0 is subnormal (M * 2^-9); 0x7F / 0xFF are NaN. */
+static float e4m3_to_f32(uint8_t c) {
+    int e = (c >> 3) & 0xF, m = c & 7;
+    float v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexpf((float)m, -9);
+    else v = ldexpf((float)(8 + m), e - 7 - 3);
+    return (c & 0x80) ? -v : v;
+}
+
+/* fp32 -> E4M3, round-to-nearest-even, saturating. */
+static uint8_t f32_to_e4m3(float f) {
+    uint8_t sign = signbit(f) ? 0x80 : 0x00;
+    float a = fabsf(f);
+    int e;
+    float q, lo, frac;
+    int r;
+    if (isnan(f)) return 0x7F;
+    if (a >= 448.0f) return (uint8_t)(sign | 0x7E);
+    if (a == 0.0f) return sign;
+    (void)frexpf(a, &e);          /* a = m * 2^e, m in [0.5, 1)  ->  a in [2^(e-1), 2^e) */
+    e -= 1;
+    if (e < -6) e = -6;           /* below the smallest normal the quantum stays 2^-9 */
+    q = ldexpf(a, 3 - e);         /* exact: in units of the quantum; [8,16) normal, [0,8) subnormal */
+    lo = floorf(q);
+    frac = q - lo;                /* exact */
+    r = (int)lo;
+    if (frac > 0.5f || (frac == 0.5f && (r & 1))) r += 1;
+    if (r == 16) { r = 8; e += 1; }
+    if (r < 8) return (uint8_t)(sign | r);                       /* subnormal (e == -6) or zero */
+    return (uint8_t)(sign | ((e + 7) << 3) | (r - 8));
+}
+
+int orc_e4m3_encode(const float* in, int64_t n, uint8_t* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = f32_to_e4m3(in[i]);
+    return 0;
+}
+int orc_e4m3_decode(const uint8_t* in, int64_t n, float* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = e4m3_to_f32(in[i]);
+    return 0;
+}
+
+/* FP8 form of S(X): Q[M,K] holds the E4M3 code of (s * x) * (1 / x_scale) at kept positions and
+ * 0 elsewhere; s is the GROUP factor (scope GROUP) or 1 (ROW / TENSOR factors are constant along
+ * the contraction and multiply Y instead, NONE has none). */
+int orc_apply_fp8(const uint16_t* X, const uint8_t* keep, const float* s, int64_t M, int64_t K,
+                  int64_t ldx, int scope, float x_scale, uint8_t* Q) {
+    const float inv = 1.0f / x_scale;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            uint8_t q = 0;
+            if (keep[m * K + k]) {
+                float v = bf16_to_f32(X[m * ldx + k]);
+                if (scope == ORC_GROUP) v = s[m * (K / 4) + k / 4] * v;
+                v = v * inv;
+                q = f32_to_e4m3(v);
+            }
+            Q[m * K + k] = q;
+        }
+    return 0;
+}
+
+/* orc_pack for one-byte elements: vals8[M,K/2], meta as in orc_pack. */
+int orc_pack8(const uint8_t* D, const uint8_t* keep, int64_t M, int64_t K, uint8_t* vals, uint8_t* meta) {
+    if (K % 8 != 0) return 1;
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t b = 0; b < K / 8; ++b) meta[m * (K / 8) + b] = 0;
+        for (int64_t g = 0; g < K / 4; ++g) {
+            int pos[2], n = 0;
+            for (int i = 0; i < 4; ++i)
+                if (keep[m * K + 4 * g + i]) { if (n < 2) pos[n] = i; ++n; }
+            if (n != 2) return 2;
+            vals[m * (K / 2) + 2 * g + 0] = D[m * K + 4 * g + pos[0]];
+            vals[m * (K / 2) + 2 * g + 1] = D[m * K + 4 * g + pos[1]];
+            unsigned nib = (unsigned)pos[0] | ((unsigned)pos[1] << 2);
+            meta[m * (K / 8) + g / 2] |= (uint8_t)(nib << (4 * (g & 1)));
+        }
+    }
     return 0;
 }
 

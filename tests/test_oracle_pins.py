@@ -280,3 +280,130 @@ def test_lora_special_cases():
     Xs = np.where(keep > 0, Xb, 0).astype(np.uint16)
     assert not np.allclose(oracle.linear_f32w(oracle.bf16_to_f32(Xs), oracle.lora_delta(Wb, eye)), dense,
                            atol=1e-3 * np.abs(dense).max())
+
+
+# ---------------------------------------------------------------- FP8 (E4M3) composition
+def test_e4m3_decode_closed_forms_and_library():
+    """Code values from the format definition (bias 7, 3 mantissa bits, subnormals, no inf) and
+    torch's own E4M3 view as a second implementation."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    dec = oracle.e4m3_decode(codes)
+    hand = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x39: 1.125,
+            0x40: 2.0, 0x64: 48.0, 0x68: 64.0, 0x7E: 448.0, 0xB8: -1.0, 0xFE: -448.0}
+    for c, v in hand.items():
+        assert dec[c] == np.float32(v), hex(c)
+    assert np.isnan(dec[0x7F]) and np.isnan(dec[0xFF])
+    assert np.signbit(dec[0x80]) and dec[0x80] == 0.0
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    ok = ~np.isnan(lib)
+    assert np.array_equal(np.isnan(dec), np.isnan(lib))
+    assert np.array_equal(dec[ok], lib[ok])
+    # positive codes are strictly increasing in value
+    assert np.all(np.diff(dec[:0x7F]) > 0)
+
+
+def test_e4m3_encode_rounding_saturation_and_library():
+    import torch
+    # round trip: every non-NaN code is a fixed point
+    codes = np.array([c for c in range(256) if c & 0x7F != 0x7F], dtype=np.uint8)
+    assert np.array_equal(oracle.e4m3_encode(oracle.e4m3_decode(codes)), codes)
+    # ties go to the even mantissa; just off a tie goes to the nearer neighbour
+    hand = [(1.0625, 0x38), (1.1875, 0x3A), (np.nextafter(np.float32(1.0625), np.float32(2)), 0x39),
+            (np.nextafter(np.float32(1.1875), np.float32(0)), 0x39),
+            (2.0 ** -10, 0x00), (3 * 2.0 ** -10, 0x02), (np.nextafter(np.float32(2.0 ** -10), np.float32(1)), 0x01),
+            (15.5 * 2.0 ** -9 / 2, 0x08),              # 7.75 quanta -> 8 quanta = smallest normal
+            (0.9999, 0x38), (-3.0594, 0xC4), (48.95, 0x64), (-65.27, 0xE8),
+            (448.0, 0x7E), (449.0, 0x7E), (463.9, 0x7E), (464.0, 0x7E), (1e9, 0x7E), (np.inf, 0x7E),
+            (-np.inf, 0xFE), (-1e30, 0xFE), (np.nan, 0x7F), (-0.0, 0x80), (1e-12, 0x00)]
+    got = oracle.e4m3_encode(np.array([h[0] for h in hand], dtype=np.float32))
+    for (v, want), g in zip(hand, got):
+        assert g == want, (v, hex(g), hex(want))
+    # second implementation: torch's conversion on everything it can represent (it has no saturation)
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(200000) * s for s in (1e-3, 0.05, 1.0, 30.0, 150.0)]).astype(np.float32)
+    x = x[np.abs(x) < 448.0]
+    lib = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(oracle.e4m3_encode(x), lib)
+    # every midpoint between neighbouring codes and its two fp32 neighbours
+    v = oracle.e4m3_decode(np.arange(0x7F, dtype=np.uint8)).astype(np.float64)
+    mids = ((v[:-1] + v[1:]) / 2).astype(np.float32)
+    pts = np.concatenate([mids, np.nextafter(mids, np.float32(0)), np.nextafter(mids, np.float32(1e9))])
+    pts = np.concatenate([pts, -pts])
+    lib = torch.from_numpy(pts).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(oracle.e4m3_encode(pts), lib)
+    # monotone
+    xs = np.sort(x)
+    assert np.all(np.diff(oracle.e4m3_decode(oracle.e4m3_encode(xs))) >= 0)
+
+
+def test_fp8_sparsify_hand_case_and_invariants():
+    # (3,-4,1,0): keeps 3 and -4, s = sqrt(26/(25+1e-8)) = 1.0198039; with x_scale 1/16 the scaled
+    # values are 48.95 and -65.27 -> 48 (0x64) and -64 (0xE8). (1,1,1,1): s = sqrt(2), 16*1.41421 = 22.63 -> 22 (0x5B)
+    Xf = np.array([[3, -4, 1, 0, 1, 1, 1, 1]], dtype=np.float32)
+    r = oracle.sparsify_pack_fp8_oracle(bf(Xf), 1.0 / 16.0, scope=oracle.GROUP)
+    assert r["keep"].tolist() == [[1, 1, 0, 0, 1, 1, 0, 0]]
+    assert r["vals"].tolist() == [[0x64, 0xE8, 0x5B, 0x5B]]
+    assert r["meta"].tolist() == [[0x44]]
+    assert r["Q"].tolist() == [[0x64, 0xE8, 0, 0, 0x5B, 0x5B, 0, 0]]
+    # without compensation the codes are those of x / x_scale: 48 and -64 exactly
+    r0 = oracle.sparsify_pack_fp8_oracle(bf(Xf), 1.0 / 16.0, scope=oracle.NONE)
+    assert r0["vals"].tolist() == [[0x64, 0xE8, 0x58, 0x58]]
+    # random input: same mask and metadata as the bf16 path, dropped entries are code 0, kept entries
+    # decode to within half a quantum (2^-4 relative) of the fp32 value they quantise
+    X, _ = synth.workload("tiny", seed=4, M=64)
+    Xb = synth.bits(X)
+    amax = np.abs(oracle.bf16_to_f32(Xb)).max()
+    x_scale = np.float32(amax * np.sqrt(2.0) / 448.0)
+    for scope in (oracle.NONE, oracle.GROUP, oracle.ROW, oracle.TENSOR):
+        r8 = oracle.sparsify_pack_fp8_oracle(Xb, x_scale, scope=scope)
+        r16 = oracle.sparsify_pack_oracle(Xb, scope=scope)
+        assert np.array_equal(r8["keep"], r16["keep"]) and np.array_equal(r8["meta"], r16["meta"])
+        assert np.all(r8["Q"][r8["keep"] == 0] == 0)
+        target = oracle.bf16_to_f32(Xb).astype(np.float64)
+        if scope == oracle.GROUP:
+            target = target * np.repeat(r8["s"].astype(np.float64), 4, axis=1)
+        target = np.where(r8["keep"] > 0, target, 0.0) / np.float64(x_scale)
+        assert np.abs(target).max() <= 448.0 * (1 + 1e-6)          # sqrt(2) * amax bounds s * x
+        dec = oracle.e4m3_decode(r8["Q"]).astype(np.float64)
+        quantum = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(target), 2.0 ** -6))) - 3), 2.0 ** -9)
+        assert np.all(np.abs(dec - target) <= 0.5 * quantum * (1 + 1e-5))
+    # saturation instead of overflow when the scale is too small
+    rs = oracle.sparsify_pack_fp8_oracle(bf(np.array([[1000, -2000, 1, 0, 0, 0, 0, 0]], dtype=np.float32)), 1.0, scope=oracle.NONE)
+    assert rs["vals"].tolist() == [[0x7E, 0xFE, 0, 0]]
+
+
+def test_fp8_sparse_linear_reduces_to_integer_matmul_and_fp64():
+    rng = np.random.default_rng(5)
+    # already 2:4 sparse small integers, integer weights, scale 1, no compensation: everything is exact
+    M, K, N = 8, 64, 16
+    Xi = rng.integers(-8, 9, size=(M, K))
+    Xi.reshape(M, K // 4, 4)[:, :, 2:] = 0
+    Xi[Xi == 0] = 1
+    Xi.reshape(M, K // 4, 4)[:, :, 2:] = 0
+    Wi = rng.integers(-8, 9, size=(N, K))
+    Wq = oracle.quantize_weights_fp8(bf(Wi.astype(np.float32)))
+    assert np.array_equal(oracle.e4m3_decode(Wq), Wi.astype(np.float32))
+    Y = oracle.sparse_linear_fp8_oracle(bf(Xi.astype(np.float32)), Wq, 1.0, scope=oracle.NONE)["Y"]
+    assert np.array_equal(Y, (Xi @ Wi.T).astype(np.float32))
+    # general input: equals the fp64 product of the decoded operands times the factors, and is
+    # not transposed; bias is added last
+    X, W = synth.workload("tiny", seed=6, M=16)
+    Xb, Wb = synth.bits(X), synth.bits(W)
+    Wq = oracle.quantize_weights_fp8(Wb)
+    bias = bf(rng.standard_normal(W.shape[0]).astype(np.float32))
+    x_scale = np.float32(np.abs(oracle.bf16_to_f32(Xb)).max() * np.sqrt(2.0) / 448.0)
+    for scope in (oracle.NONE, oracle.GROUP, oracle.ROW, oracle.TENSOR):
+        r = oracle.sparse_linear_fp8_oracle(Xb, Wq, x_scale, bias=bias, scope=scope)
+        f = np.float64(x_scale)
+        if scope == oracle.ROW:
+            f = f * r["s"].astype(np.float64)[:, None]
+        elif scope == oracle.TENSOR:
+            f = f * np.float64(r["s"][0])
+        ref = f * (oracle.e4m3_decode(r["Q"]).astype(np.float64) @ oracle.e4m3_decode(Wq).astype(np.float64).T)
+        ref = ref + oracle.bf16_to_f32(bias).astype(np.float64)[None, :]
+        assert np.allclose(r["Y"], ref, rtol=0, atol=3e-5 * np.abs(ref).max())
+    # the quantised path approximates the bf16 sparse path (sanity, not a gate of the paper)
+    y16 = oracle.sparse_linear_oracle(Xb, Wb, scope=oracle.GROUP)["Y"]
+    y8 = oracle.sparse_linear_fp8_oracle(Xb, Wq, x_scale, scope=oracle.GROUP)["Y"]
+    assert oracle.rfe(y16, y8) < 0.1
