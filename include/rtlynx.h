@@ -149,6 +149,46 @@ rtl_status rtl_dense_linear(const void* X, const void* W, const void* bias, void
                             int64_t ldx, int64_t ldw, int64_t ldy,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * FP8 composition (implementation details, "orthogonal validation with FP8 quantization": symmetric
+ * FP8 quantisation of the activations, weights cast directly to FP8; 2:4 FP8 is one of the formats
+ * of the App. A table). FP8 is E4M3 without infinities (bias 7, largest finite 448, S.1111.111 =
+ * NaN); every conversion is round-to-nearest-even and saturating (|v| >= 448 and +-inf give +-448,
+ * NaN gives 0x7F).
+ *
+ * rtl_quantize_fp8 - the direct cast of the weights: Wq[r, c] = e4m3(W[r, c]).
+ *   W [rows, cols] bf16 (ld), 16-byte aligned, ld % 8 == 0; Wq [rows, cols] bytes (ldq), 8-byte
+ *   aligned, ldq % 8 == 0; cols % 8 == 0.
+ *
+ * rtl_sparsify_pack_fp8 - rtl_sparsify_pack with FP8 kept values. Selection, metadata, `scale`
+ *   and the workspace are exactly those of rtl_sparsify_pack (they look at the bf16 input only).
+ *   x_scale  fp32 [1] on the device, > 0: the symmetric activation scale (one per tensor, supplied
+ *            by the caller, e.g. calibrated max|S(X)| / 448).
+ *   vals     [M, K/2] bytes, 4-byte aligned: e4m3((s_g * x) * (1 / x_scale[0])) for GROUP (s_g as in
+ *            rtl_sparsify_pack, both products in fp32, one rounding), e4m3(x * (1 / x_scale[0])) otherwise.
+ *
+ * rtl_sparse_linear_fp8 - W8A8 + 2:4 activation sparsity:
+ *     Y = f * (Q Wq^T) (+ b),  Q = the quantised S(X) above,  f = x_scale[0] (times the ROW / TENSOR factor),
+ *   on the FP8 structured-sparse matrix instruction, fp32 accumulation, bf16 output.
+ *   X [M,K] bf16 (ldx) as for rtl_sparse_linear; Wq [N,K] E4M3 bytes (ldw >= K, ldw % 16 == 0,
+ *   16-byte aligned); K % 128 == 0; bias NULL or bf16 [N]; Y [M,N] bf16 (ldy).
+ *   workspace  rtl_sparse_linear_fp8_workspace(M, N, K, comp) bytes, 256-byte aligned.
+ * ------------------------------------------------------------------------------------------- */
+rtl_status rtl_quantize_fp8(const void* W, int64_t rows, int64_t cols, int64_t ld,
+                            void* Wq, int64_t ldq, void* stream);
+size_t rtl_sparsify_pack_fp8_workspace(int64_t M, int64_t K, rtl_comp comp);
+rtl_status rtl_sparsify_pack_fp8(const void* X, int64_t M, int64_t K, int64_t ldx,
+                                 rtl_comp comp, float eps, const float* x_scale,
+                                 void* vals, void* meta, float* scale,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+size_t rtl_sparse_linear_fp8_workspace(int64_t M, int64_t N, int64_t K, rtl_comp comp);
+rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_scale,
+                                 const void* bias, void* Y,
+                                 int64_t M, int64_t N, int64_t K,
+                                 int64_t ldx, int64_t ldw, int64_t ldy,
+                                 rtl_comp comp, float eps,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* Human-readable name of a status code; never NULL. */
 const char* rtl_status_str(rtl_status s);
 /* Library version string, e.g. "rtlynx-gfx950 0.1". */

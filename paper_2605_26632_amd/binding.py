@@ -18,7 +18,10 @@ COMP = {"none": COMP_NONE, "group": COMP_GROUP, "row": COMP_ROW, "tensor": COMP_
 SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linear_workspace",
            "rtl_packed_linear", "rtl_sparse_linear_workspace", "rtl_sparse_linear",
            "rtl_sparse_lora_linear_workspace", "rtl_sparse_lora_linear",
-           "rtl_dense_linear_workspace", "rtl_dense_linear", "rtl_status_str", "rtl_version"]
+           "rtl_dense_linear_workspace", "rtl_dense_linear",
+           "rtl_quantize_fp8", "rtl_sparsify_pack_fp8_workspace", "rtl_sparsify_pack_fp8",
+           "rtl_sparse_linear_fp8_workspace", "rtl_sparse_linear_fp8",
+           "rtl_status_str", "rtl_version"]
 
 _lib = None
 
@@ -59,6 +62,16 @@ def lib():
         L.rtl_dense_linear_workspace.restype = sz
         L.rtl_dense_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, sz, vp]
         L.rtl_dense_linear.restype = ci
+        L.rtl_quantize_fp8.argtypes = [vp, i64, i64, i64, vp, i64, vp]
+        L.rtl_quantize_fp8.restype = ci
+        L.rtl_sparsify_pack_fp8_workspace.argtypes = [i64, i64, ci]
+        L.rtl_sparsify_pack_fp8_workspace.restype = sz
+        L.rtl_sparsify_pack_fp8.argtypes = [vp, i64, i64, i64, ci, fl, vp, vp, vp, vp, vp, sz, vp]
+        L.rtl_sparsify_pack_fp8.restype = ci
+        L.rtl_sparse_linear_fp8_workspace.argtypes = [i64, i64, i64, ci]
+        L.rtl_sparse_linear_fp8_workspace.restype = sz
+        L.rtl_sparse_linear_fp8.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, fl, vp, sz, vp]
+        L.rtl_sparse_linear_fp8.restype = ci
         L.rtl_status_str.argtypes = [ci]
         L.rtl_status_str.restype = C.c_char_p
         L.rtl_version.restype = C.c_char_p
@@ -188,4 +201,62 @@ def dense_linear(X, W, bias=None, out=None, ws=None):
     st = L.rtl_dense_linear(_p(X), _p(W), _p(bias), _p(Y), M, N, K, X.stride(0), W.stride(0),
                             Y.stride(0), _p(ws), ws.numel(), _stream())
     _check(st, "rtl_dense_linear")
+    return Y
+
+
+# ---- FP8 (E4M3) composition; codes travel as uint8 tensors ----------------------------------
+
+def quantize_fp8(W, out=None):
+    """rtl_quantize_fp8: bf16 [rows, cols] -> E4M3 codes (uint8), direct cast."""
+    _need_cuda(W)
+    assert W.dtype == torch.bfloat16 and W.dim() == 2 and W.stride(1) == 1
+    rows, cols = W.shape
+    Wq = torch.empty((rows, cols), dtype=torch.uint8, device=W.device) if out is None else out
+    st = lib().rtl_quantize_fp8(_p(W), rows, cols, W.stride(0), _p(Wq), Wq.stride(0), _stream())
+    _check(st, "rtl_quantize_fp8")
+    return Wq
+
+
+def sparsify_pack_fp8(X, x_scale, comp=COMP_GROUP, eps=1e-8, out=None):
+    """rtl_sparsify_pack_fp8: X bf16 [M,K], x_scale fp32 [1] -> (vals u8 [M,K/2], meta u8 [M,K/8], scale)."""
+    _need_cuda(X, x_scale)
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.stride(1) == 1
+    assert x_scale.dtype == torch.float32
+    M, K = X.shape
+    dev = X.device
+    if out is None:
+        vals = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        meta = torch.empty((M, K // 8), dtype=torch.uint8, device=dev)
+    else:
+        vals, meta = out
+    scale = None
+    if comp == COMP_ROW:
+        scale = torch.empty((M,), dtype=torch.float32, device=dev)
+    elif comp == COMP_TENSOR:
+        scale = torch.empty((1,), dtype=torch.float32, device=dev)
+    L = lib()
+    ws = _ws(L.rtl_sparsify_pack_fp8_workspace(M, K, comp), dev)
+    st = L.rtl_sparsify_pack_fp8(_p(X), M, K, X.stride(0), comp, eps, _p(x_scale), _p(vals), _p(meta),
+                                 _p(scale), _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_sparsify_pack_fp8")
+    return vals, meta, scale
+
+
+def sparse_linear_fp8_workspace(M, N, K, comp=COMP_GROUP):
+    return int(lib().rtl_sparse_linear_fp8_workspace(M, N, K, comp))
+
+
+def sparse_linear_fp8(X, Wq, x_scale, bias=None, comp=COMP_GROUP, eps=1e-8, out=None, ws=None):
+    """rtl_sparse_linear_fp8: Y = x_scale * (e4m3(S(X) / x_scale) Wq^T) (+ bias), bf16 [M,N]."""
+    _need_cuda(X, Wq, x_scale)
+    assert Wq.dtype == torch.uint8 and x_scale.dtype == torch.float32
+    M, K = X.shape
+    N = Wq.shape[0]
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if out is None else out
+    L = lib()
+    if ws is None:
+        ws = _ws(L.rtl_sparse_linear_fp8_workspace(M, N, K, comp), X.device)
+    st = L.rtl_sparse_linear_fp8(_p(X), _p(Wq), _p(x_scale), _p(bias), _p(Y), M, N, K, X.stride(0),
+                                 Wq.stride(0), Y.stride(0), comp, eps, _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_sparse_linear_fp8")
     return Y

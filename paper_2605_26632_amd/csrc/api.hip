@@ -15,12 +15,12 @@ inline bool eps_ok(float e) { return std::isfinite(e) && e >= 0.0f; }
 struct SparseWs {
     size_t vals, meta, scale, pack, gemm, total;
 };
-SparseWs sparse_ws(int64_t M, int64_t N, int64_t K, rtl_comp comp) {
+SparseWs sparse_ws(int64_t M, int64_t N, int64_t K, rtl_comp comp, size_t val_bytes = 2) {
     SparseWs w{};
     size_t off = 0;
-    w.vals = off; off += round_up((size_t)M * (size_t)(K / 2) * 2, 256);
+    w.vals = off; off += round_up((size_t)M * (size_t)(K / 2) * val_bytes, 256);
     w.meta = off; off += round_up(rtl::kmajor_bytes(M, K), 256);
-    w.scale = off; off += round_up((size_t)(M > 0 ? M : 1) * sizeof(float), 256);
+    w.scale = off; off += round_up((size_t)((M > 0 ? M : 1) + 1) * sizeof(float), 256);   // + one fused scalar
     w.pack = off; off += round_up(rtl_sparsify_pack_workspace(M, K, comp), 256);
     w.gemm = off; off += round_up(rtl::gemm_workspace_bytes(true, M, N, K), 256);
     w.total = off;
@@ -74,14 +74,15 @@ rtl_status rtl_sparsify_pack(const void* X, int64_t M, int64_t K, int64_t ldx, r
 }
 
 static rtl_status check_linear(const void* A, const void* W, const void* Y, int64_t M, int64_t N,
-                               int64_t K, int64_t lda, int64_t ldw, int64_t ldy, int64_t a_extent) {
-    if (M < 0 || N < 0 || K <= 0 || K % 64 != 0 || lda < a_extent || ldw < K || ldy < N)
+                               int64_t K, int64_t lda, int64_t ldw, int64_t ldy, int64_t a_extent,
+                               int64_t k_granule = 64, int64_t ldw_granule = 8) {
+    if (M < 0 || N < 0 || K <= 0 || K % k_granule != 0 || lda < a_extent || ldw < K || ldy < N)
         return RTL_ERR_SHAPE;
     if (M > ((int64_t)1 << 30) || N > ((int64_t)1 << 30) || K > ((int64_t)1 << 30))
         return RTL_ERR_SHAPE;
     if (M == 0 || N == 0) return RTL_OK;
     if (!A || !W || !Y) return RTL_ERR_NULL;
-    if (lda % 8 != 0 || ldw % 8 != 0 || !aligned(A, 16) || !aligned(W, 16) || !aligned(Y, 2))
+    if (lda % 8 != 0 || ldw % ldw_granule != 0 || !aligned(A, 16) || !aligned(W, 16) || !aligned(Y, 2))
         return RTL_ERR_ALIGN;
     return RTL_OK;
 }
@@ -104,13 +105,13 @@ rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* ro
     if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
     rtl::GemmArgs g{};
-    g.A = static_cast<const uint16_t*>(vals);
+    g.A = vals;
     uint8_t* km = static_cast<uint8_t*>(workspace);
     hipError_t e = rtl::launch_meta_to_kmajor(static_cast<const uint8_t*>(meta), M, K, km,
                                               static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return RTL_ERR_HIP;
     g.meta = km;
-    g.W = static_cast<const uint16_t*>(W);
+    g.W = W;
     g.bias = static_cast<const uint16_t*>(bias);
     g.row_scale = row_scale;
     g.tensor_scale = tensor_scale;
@@ -146,9 +147,9 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
         reinterpret_cast<float*>(base + ws.pack), s);
     if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};
-    g.A = reinterpret_cast<const uint16_t*>(base + ws.vals);
+    g.A = base + ws.vals;
     g.meta = base + ws.meta;
-    g.W = static_cast<const uint16_t*>(W);
+    g.W = W;
     g.bias = static_cast<const uint16_t*>(bias);
     g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
     g.tensor_scale = comp == RTL_COMP_TENSOR ? scale : nullptr;
@@ -197,9 +198,9 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
                                   scale, reinterpret_cast<float*>(base + ws.pack), s);
     if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};
-    g.A = reinterpret_cast<const uint16_t*>(base + ws.vals);
+    g.A = base + ws.vals;
     g.meta = base + ws.meta;
-    g.W = static_cast<const uint16_t*>(W);
+    g.W = W;
     g.bias = static_cast<const uint16_t*>(bias);
     g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
     g.tensor_scale = comp == RTL_COMP_TENSOR ? scale : nullptr;
@@ -208,6 +209,86 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
     g.T = T;
     g.LA = static_cast<const uint16_t*>(LA);
     g.ldla = ldla;
+    e = rtl::launch_gemm(true, g, s);
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+// ---- FP8 (E4M3) composition -------------------------------------------------------------------
+
+rtl_status rtl_quantize_fp8(const void* W, int64_t rows, int64_t cols, int64_t ld, void* Wq,
+                            int64_t ldq, void* stream) {
+    if (rows < 0 || cols < 0 || cols % 8 != 0 || ld < cols || ldq < cols) return RTL_ERR_SHAPE;
+    if (rows > ((int64_t)1 << 30) || cols > ((int64_t)1 << 30)) return RTL_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return RTL_OK;
+    if (!W || !Wq) return RTL_ERR_NULL;
+    if (ld % 8 != 0 || ldq % 8 != 0 || !aligned(W, 16) || !aligned(Wq, 8)) return RTL_ERR_ALIGN;
+    hipError_t e = rtl::launch_quantize_fp8(static_cast<const uint16_t*>(W), rows, cols, ld,
+                                            static_cast<uint8_t*>(Wq), ldq,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+size_t rtl_sparsify_pack_fp8_workspace(int64_t M, int64_t K, rtl_comp comp) {
+    return rtl_sparsify_pack_workspace(M, K, comp);
+}
+
+rtl_status rtl_sparsify_pack_fp8(const void* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
+                                 float eps, const float* x_scale, void* vals, void* meta,
+                                 float* scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    if (M < 0 || K < 0 || K % 8 != 0 || ldx < K || K > (int64_t)1 << 30) return RTL_ERR_SHAPE;
+    if (M == 0 || K == 0) return RTL_OK;
+    if (!X || !vals || !meta || !x_scale) return RTL_ERR_NULL;
+    if ((comp == RTL_COMP_ROW || comp == RTL_COMP_TENSOR) && !scale) return RTL_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned(X, 16) || !aligned(vals, 4) || !aligned(meta, 4) || !aligned(x_scale, 4))
+        return RTL_ERR_ALIGN;
+    if (scale && !aligned(scale, 4)) return RTL_ERR_ALIGN;
+    const size_t need = rtl_sparsify_pack_fp8_workspace(M, K, comp);
+    if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
+    if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    hipError_t e = rtl::launch_sparsify_pack_fp8(
+        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, x_scale, static_cast<uint8_t*>(vals),
+        static_cast<uint8_t*>(meta), nullptr, scale, static_cast<float*>(workspace), nullptr,
+        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+size_t rtl_sparse_linear_fp8_workspace(int64_t M, int64_t N, int64_t K, rtl_comp comp) {
+    if (M <= 0 || N <= 0 || K <= 0 || !comp_ok(comp)) return 0;
+    return sparse_ws(M, N, K, comp, 1).total;
+}
+
+rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_scale, const void* bias,
+                                 void* Y, int64_t M, int64_t N, int64_t K, int64_t ldx, int64_t ldw,
+                                 int64_t ldy, rtl_comp comp, float eps, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    rtl_status st = check_linear(X, Wq, Y, M, N, K, ldx, ldw, ldy, K, 128, 16);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (!x_scale) return RTL_ERR_NULL;
+    if ((bias && !aligned(bias, 2)) || !aligned(x_scale, 4)) return RTL_ERR_ALIGN;
+    const SparseWs ws = sparse_ws(M, N, K, comp, 1);
+    if (!workspace || workspace_bytes < ws.total) return RTL_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    float* scale = reinterpret_cast<float*>(base + ws.scale);
+    float* fused = scale + (comp == RTL_COMP_ROW ? M : 1);   // x_scale times the TENSOR factor
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = rtl::launch_sparsify_pack_fp8(
+        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, x_scale, base + ws.vals, nullptr,
+        base + ws.meta, scale, reinterpret_cast<float*>(base + ws.pack), fused, s);
+    if (e != hipSuccess) return RTL_ERR_HIP;
+    rtl::GemmArgs g{};
+    g.fp8 = true;
+    g.A = base + ws.vals;
+    g.meta = base + ws.meta;
+    g.W = Wq;
+    g.bias = static_cast<const uint16_t*>(bias);
+    g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
+    g.tensor_scale = comp == RTL_COMP_TENSOR ? fused : x_scale;   // dequantisation rides on the epilogue
+    g.Y = static_cast<uint16_t*>(Y);
+    g.partials = reinterpret_cast<float*>(base + ws.gemm);
+    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, s);
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
@@ -227,8 +308,8 @@ rtl_status rtl_dense_linear(const void* X, const void* W, const void* bias, void
     if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
     rtl::GemmArgs g{};
-    g.A = static_cast<const uint16_t*>(X);
-    g.W = static_cast<const uint16_t*>(W);
+    g.A = X;
+    g.W = W;
     g.bias = static_cast<const uint16_t*>(bias);
     g.Y = static_cast<uint16_t*>(Y);
     g.partials = static_cast<float*>(workspace);

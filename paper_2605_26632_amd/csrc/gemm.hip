@@ -24,6 +24,16 @@
 // v_mfma_f32_32x32x16_bf16: A and B (8 bf16) hold k = 8 kb + v of row / column i; D as above.
 // The labelling of k inside a stage is free as long as both operands agree; it is chosen so that
 // a lane reads whole 16-byte chunks from LDS and one 32-bit word of metadata per stage.
+//
+// FP8 variant of the sparse kernel (E4M3 codes on both operands, the W8A8 composition of the
+// implementation-details section): v_smfmac_f32_32x32x64_fp8_fp8, measured the same way:
+//   A (16 fp8)  : row i, the kept values of dense k in [32 kb, 32 kb + 32) in order
+//   idx (32 bit): the whole register, nibble g = pos0 | pos1 << 2 of the lane's g-th group
+//   B (32 fp8)  : column i; element u < 16 is dense k = 16 kb + u, u >= 16 is k = 32 + 16 kb + (u - 16)
+//   D           : as above
+// In bytes this is the bf16 geometry (16-byte A chunk, two 16-byte B chunks at the same chunk
+// indices), so a stage simply covers 128 dense k instead of 64 and the kernel differs only in the
+// instruction and in the metadata record (16 bytes per row and stage, one 32-bit word per sub-step).
 #include <type_traits>
 #include "rtl_internal.h"
 
@@ -33,14 +43,18 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 union Frag8 {
     uint4 u;
     bf16x8 v;
+    i32x4 q;     // 16 fp8
 };
 union Frag16 {
     uint4 u[2];
     bf16x16 v;
+    i32x8 q;     // 32 fp8
 };
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
@@ -86,10 +100,11 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0() {   // vmcnt <= N, all LDS re
 
 // Per-stage LDS footprint. Rows of the A tile hold 64 bytes in both kernels (32 kept bf16 of 64
 // dense k, or 32 dense k); rows of the B tile hold 128 bytes (sparse) or 64 bytes (dense).
-template <bool SPARSE, int BM, int BN, int STAGES, int WAVES_M = 1, int WAVES_N = 1>
+template <bool SPARSE, int BM, int BN, int STAGES, int WAVES_M = 1, int WAVES_N = 1, bool FP8 = false>
 struct Smem {
     static constexpr int kABytes = BM * 64;
-    static constexpr int kMetaBytes = SPARSE ? BM * 8 : 0;
+    static constexpr int kMetaRec = FP8 ? 16 : 8;   // metadata bytes per row and stage
+    static constexpr int kMetaBytes = SPARSE ? BM * kMetaRec : 0;
     static constexpr int kBBytes = SPARSE ? BN * 128 : BN * 64;
     static constexpr int kStage = kABytes + kMetaBytes + kBBytes;
     static constexpr int kRing = STAGES * kStage;
@@ -138,21 +153,25 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
 
 // MODE 0: plain linear. MODE 1 (sparse only): LoRA tail, the accumulators also receive T L_A^T before
 // the epilogue. MODE 2: split contraction, grid.y K ranges, fp32 partial tiles instead of Y.
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0>
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
     static_assert(MODE == 0 || (MODE == 1 && SPARSE) || (MODE == 2 && !SPARSE), "mode/operand combination");
+    static_assert(!FP8 || (SPARSE && MODE == 0), "FP8 operands: plain sparse kernel only");
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
-    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N>;
-    constexpr int KSTAGE = SPARSE ? 64 : 32;          // dense k per stage
-    constexpr int A_ELEMS = 32;                       // bf16 of an A row per stage (both kernels)
+    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8>;
+    constexpr int ESZ = FP8 ? 1 : 2;                  // bytes per operand element
+    constexpr int KSTAGE = SPARSE ? 128 / ESZ : 32;   // dense k per stage
+    constexpr int A_ELEMS = 64 / ESZ;                 // elements of an A row per stage: 64 bytes
+    constexpr int MREC = L::kMetaRec;                 // metadata bytes per row and stage
+    constexpr int IXW = FP8 ? 2 : 1;                  // metadata words a lane holds per stage and row block
     // one wave-wide direct-to-LDS load moves 64 chunks of 16 bytes = 1 KiB
     constexpr int A_LOADS = L::kABytes / 1024, B_LOADS = L::kBBytes / 1024;
     static_assert(A_LOADS % NW == 0 && B_LOADS % NW == 0, "tile loads must divide over the waves");
     constexpr int A_PER_W = A_LOADS / NW, B_PER_W = B_LOADS / NW;
-    constexpr int M_LOADS = SPARSE ? (BM * 8) / 256 : 0;  // metadata: 4 bytes per lane per load
+    constexpr int M_LOADS = SPARSE ? (BM * MREC) / 256 : 0;  // metadata: 4 bytes per lane per load
     static_assert(!SPARSE || M_LOADS % NW == 0, "metadata loads must divide over the waves");
     constexpr int M_PER_W = M_LOADS / NW;
 
@@ -185,8 +204,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     // ---- global -> LDS: every lane owns fixed chunks; rows past the edge are clamped to the last
     //      valid row (their products only reach outputs that are never stored) -----------------
     // wave-uniform bases of this tile's three streams, already advanced to the first stage
-    const uint8_t* base_a = reinterpret_cast<const uint8_t*>(a.A + m0 * a.lda + (int64_t)kt_first * A_ELEMS);
-    const uint8_t* base_b = reinterpret_cast<const uint8_t*>(a.W + n0 * a.ldw + (int64_t)kt_first * KSTAGE);
+    const uint8_t* base_a = static_cast<const uint8_t*>(a.A) + (m0 * a.lda + (int64_t)kt_first * A_ELEMS) * ESZ;
+    const uint8_t* base_b = static_cast<const uint8_t*>(a.W) + (n0 * a.ldw + (int64_t)kt_first * KSTAGE) * ESZ;
     const int64_t rows_a = a.M - m0, rows_b = a.N - n0;     // valid rows from the tile's first row
     uint32_t oa[A_PER_W];
 #pragma unroll
@@ -195,7 +214,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         int row, c;
         unswz4(p, row, c);
         const int64_t gr = min((int64_t)row, rows_a - 1);
-        oa[s] = (uint32_t)(gr * a.lda * 2 + c * 16);
+        oa[s] = (uint32_t)(gr * a.lda * ESZ + c * 16);
     }
     uint32_t ob[B_PER_W];
 #pragma unroll
@@ -204,18 +223,18 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         int row, c;
         if constexpr (SPARSE) unswz8(p, row, c); else unswz4(p, row, c);
         const int64_t gr = min((int64_t)row, rows_b - 1);
-        ob[s] = (uint32_t)(gr * a.ldw * 2 + c * 16);
+        ob[s] = (uint32_t)(gr * a.ldw * ESZ + c * 16);
     }
     const uint8_t* base_m = nullptr;
     uint32_t om = 0;
     if constexpr (SPARSE) {
-        // k-major records: the 256 rows of this tile are one contiguous 2 KiB run per stage and
-        // wave w moves its 256-byte share (rows 32 w .. 32 w + 31), 4 bytes per lane
-        base_m = a.meta + m0 * 8;
-        om = (uint32_t)(wave * (32 * M_PER_W) * 8 + lane * 4);
+        // k-major records: the rows of this tile are one contiguous run per stage (2 KiB, 4 KiB with
+        // FP8 operands) and wave w moves M_PER_W 256-byte pieces of it, 4 bytes per lane
+        base_m = a.meta + m0 * MREC;
+        om = (uint32_t)(wave * M_PER_W * 256 + lane * 4);
     }
 
-    const int64_t meta_stride = ((a.M + 255) / 256 * 256) * 8;   // bytes between 64-k blocks
+    const int64_t meta_stride = ((a.M + 255) / 256 * 256) * MREC;   // bytes between stage blocks
     // Load number n (0 .. LOADS_PER_STAGE-1) of this wave for stage kt into ring buffer `stage`.
     // The loads of a stage are issued one at a time between matrix instructions: the texture
     // addresser takes a wave-wide 1 KiB request every ~16 cycles and a wave stalls at a request
@@ -224,10 +243,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         constexpr int n = decltype(n_tag)::value;
         const uint32_t base = lds0 + stage * L::kStage;
         if constexpr (n < A_PER_W) {
-            lds_dma16_so(base_a + (int64_t)kt * (A_ELEMS * 2), oa[n], base + (wave * A_PER_W + n) * 1024);
+            lds_dma16_so(base_a + (int64_t)kt * (A_ELEMS * ESZ), oa[n], base + (wave * A_PER_W + n) * 1024);
         } else if constexpr (n < A_PER_W + B_PER_W) {
             constexpr int s = n - A_PER_W;
-            lds_dma16_so(base_b + (int64_t)kt * (KSTAGE * 2), ob[s],
+            lds_dma16_so(base_b + (int64_t)kt * (KSTAGE * ESZ), ob[s],
                          base + L::kABytes + L::kMetaBytes + (wave * B_PER_W + s) * 1024);
         } else if constexpr (SPARSE && n < A_PER_W + B_PER_W + M_PER_W) {
             constexpr int s = n - A_PER_W - B_PER_W;
@@ -274,7 +293,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         Frag8 a[TM];
         Frag16 b[TN];   // dense kernel uses b[j].u[0] only
     };
-    int ix_cur[TM], ix_nxt[TM];   // metadata words of the current / next stage (sparse only)
+    // metadata words of the current / next stage (sparse only); FP8: word 2 i + sub of row block i
+    int ix_cur[TM * IXW], ix_nxt[TM * IXW];
 
     auto read_frags = [&](int stage, int sub, Frags& f) {
         const uint8_t* base = smem + stage * L::kStage;
@@ -293,23 +313,36 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
             }
         }
     };
-    auto read_idx = [&](int stage, int (&ix)[TM]) {
+    auto read_idx = [&](int stage, int (&ix)[TM * IXW]) {
         if constexpr (SPARSE) {
             const uint8_t* bM = smem + stage * L::kStage + L::kABytes;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                ix[i] = *reinterpret_cast<const int*>(bM + (arow0 + i * 32) * 8 + kb * 4);
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (FP8) {
+                    const int2 w = *reinterpret_cast<const int2*>(bM + (arow0 + i * 32) * 16 + kb * 8);
+                    ix[2 * i] = w.x;
+                    ix[2 * i + 1] = w.y;
+                } else {
+                    ix[i] = *reinterpret_cast<const int*>(bM + (arow0 + i * 32) * 8 + kb * 4);
+                }
+            }
         }
     };
     // Read number n of the fragment set of (stage, SUB), in the order the matrix instructions need
     // them: metadata words (sub-step 0 only), A fragments, then B fragments column block by block.
-    auto read_one = [&](int stage, auto sub_tag, Frags& f, int (&ix)[TM], auto n_tag) {
+    auto read_one = [&](int stage, auto sub_tag, Frags& f, int (&ix)[TM * IXW], auto n_tag) {
         constexpr int SUB = decltype(sub_tag)::value, n = decltype(n_tag)::value;
         constexpr int NI = (SPARSE && SUB == 0) ? TM : 0;     // metadata reads first
         const uint8_t* base = smem + stage * L::kStage;
         const uint8_t* bB = base + L::kABytes + L::kMetaBytes;
         if constexpr (n < NI) {
-            ix[n] = *reinterpret_cast<const int*>(base + L::kABytes + (arow0 + n * 32) * 8 + kb * 4);
+            if constexpr (FP8) {
+                const int2 w = *reinterpret_cast<const int2*>(base + L::kABytes + (arow0 + n * 32) * 16 + kb * 8);
+                ix[2 * n] = w.x;
+                ix[2 * n + 1] = w.y;
+            } else {
+                ix[n] = *reinterpret_cast<const int*>(base + L::kABytes + (arow0 + n * 32) * 8 + kb * 4);
+            }
         } else if constexpr (n < NI + TM) {
             constexpr int i = n - NI;
             f.a[i].u = *reinterpret_cast<const uint4*>(
@@ -322,11 +355,14 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
             f.b[j].u[0] = *reinterpret_cast<const uint4*>(bB + swz4(brow0 + j * 32, 2 * SUB + kb));
         }
     };
-    auto mma_one = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto n_tag) {
+    auto mma_one = [&](const Frags& f, const int (&ix)[TM * IXW], auto sub_tag, auto n_tag) {
         constexpr int SUB = decltype(sub_tag)::value;
         constexpr int n = decltype(n_tag)::value, i = n % TM, j = n / TM;
         if constexpr (n < TM * TN) {
-            if constexpr (SPARSE)
+            if constexpr (FP8)
+                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(f.a[i].q, f.b[j].q, acc[i][j],
+                                                                         ix[2 * i + SUB], 0, 0);
+            else if constexpr (SPARSE)
                 acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[i].v, f.b[j].v, acc[i][j],
                                                                       ix[i], 0, SUB);
             else
@@ -339,8 +375,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     // ring-refill requests LO <= n < HI of stage kt_load into ring buffer buf. Spreading both keeps
     // the LDS command queue and the texture addresser from filling up, which would stall the wave
     // in front of its next matrix instruction.
-    auto mma = [&](const Frags& f, const int (&ix)[TM], auto sub_tag, auto read_tag, auto rsub_tag,
-                   int rstage, Frags& rf, int (&rix)[TM], auto lo_tag, auto hi_tag, int kt_load, int buf) {
+    auto mma = [&](const Frags& f, const int (&ix)[TM * IXW], auto sub_tag, auto read_tag, auto rsub_tag,
+                   int rstage, Frags& rf, int (&rix)[TM * IXW], auto lo_tag, auto hi_tag, int kt_load, int buf) {
         constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
         constexpr bool READ = decltype(read_tag)::value;
         static_assert(TM * TN <= 16 && HI - LO <= TM * TN, "unrolled by hand up to 16 matrix instructions");
@@ -414,7 +450,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         else mma(f1, ix_cur, s1{}, std::integral_constant<bool, HAS_NEXT>{}, s0{}, nxt, f0, ix_nxt, c0{}, c0{}, 0, 0);
         if constexpr (SPARSE && HAS_NEXT) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) ix_cur[i] = ix_nxt[i];
+            for (int i = 0; i < TM * IXW; ++i) ix_cur[i] = ix_nxt[i];
         }
         cur = nxt;
     };
@@ -632,10 +668,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     }
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0>
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
-    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N>;
-    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE>;
+    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8>;
+    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8>;
     static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -680,6 +716,10 @@ static bool prefer_192(int64_t M, int64_t N) {
 }
 
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
+    if (sparse && a.fp8) {
+        if (prefer_192(a.M, a.N)) return launch_cfg<true, 256, 192, 4, 2, 3, 0, true>(a, stream);
+        return launch_cfg<true, 256, 256, 2, 4, 3, 0, true>(a, stream);
+    }
     if (sparse) {
         const bool lora = a.T != nullptr;
         if (prefer_192(a.M, a.N)) {

@@ -32,9 +32,24 @@ struct GroupOut {
     float num, den;   // sum of squares of the four / of the two kept
 };
 
-// d0 = x0 | x1 << 16, d1 = x2 | x3 << 16 (bf16 bit patterns).
-template <int COMP>
-__device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float eps) {
+// Two fp32 values -> two E4M3 codes (low byte = first): round to nearest even, saturating at
+// +-448 (so do +-inf), NaN -> 0x7F. The hardware conversion is exact for |t| <= 448 but turns
+// larger magnitudes into NaN codes, hence the clamp.
+__device__ __forceinline__ uint32_t e4m3_pair(float t0, float t1) {
+    const float c0 = __builtin_amdgcn_fmed3f(t0, -448.f, 448.f);
+    const float c1 = __builtin_amdgcn_fmed3f(t1, -448.f, 448.f);
+    uint32_t p = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(c0, c1, 0, false) & 0xFFFFu;
+    if (__builtin_isunordered(t0, t1)) {   // rare: at least one NaN
+        if (t0 != t0) p = (p & 0xFF00u) | 0x7Fu;
+        if (t1 != t1) p = (p & 0x00FFu) | 0x7F00u;
+    }
+    return p;
+}
+
+// d0 = x0 | x1 << 16, d1 = x2 | x3 << 16 (bf16 bit patterns). With FP8 the kept pair leaves as two
+// E4M3 codes of (s * x) * inv (inv = 1 / x_scale) in the low 16 bits of `packed`.
+template <int COMP, bool FP8 = false>
+__device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float eps, float inv = 1.0f) {
     // Magnitude keys made unique by appending (3 - position): the larger composite key wins,
     // so equal magnitudes resolve to the lower position.
     const uint32_t c0 = ((d0 & 0x7FFFu) << 2) | 3u;
@@ -78,6 +93,26 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
             // tiny (but non-zero) or huge / non-finite scopes are left to the exact sequence too
             const uint32_t nb = __float_as_uint(o.num);
             const bool odd_range = (nb - 0x0D800000u >= 0x63800000u) & (nb != 0u);
+            if constexpr (FP8) {
+                // Same idea one rounding later: t = p * inv is what gets rounded, to 3 mantissa
+                // bits. The fast and the exact p differ by at most 7 units, which the common
+                // multiplication by inv and its own rounding turn into at most 15 units of t, so
+                // the exact sequence runs when a fast t lies within 16 units of an E4M3 rounding
+                // boundary of the normal range (low 20 bits = 0x80000), or falls into the
+                // subnormal range of the format (0 < |t| < 2^-6), where the boundaries sit elsewhere.
+                float t0 = p0 * inv, t1 = p1 * inv;
+                const uint32_t b0 = __float_as_uint(t0), b1 = __float_as_uint(t1);
+                const uint32_t w0 = (b0 + 16u) & 0xFFFFFu, w1 = (b1 + 16u) & 0xFFFFFu;
+                const bool near8 = (w0 - 0x80000u < 32u) | (w1 - 0x80000u < 32u);
+                const bool tiny = (((b0 & 0x7FFFFFFFu) - 1u) < 0x3C7FFFFFu) | (((b1 & 0x7FFFFFFFu) - 1u) < 0x3C7FFFFFu);
+                if (near8 | tiny | odd_range) {
+                    s = sqrtf(o.num / d);
+                    t0 = (s * ka) * inv;
+                    t1 = (s * kb) * inv;
+                }
+                o.packed = e4m3_pair(t0, t1);
+                return o;
+            }
             if (near | odd_range) {
                 s = sqrtf(o.num / d);
                 p0 = s * ka;
@@ -90,6 +125,10 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
             o.packed = __builtin_bit_cast(uint32_t, pb);
             return o;
         }
+    }
+    if constexpr (FP8) {
+        o.packed = e4m3_pair(bits_to_f32(v0 << 16) * inv, bits_to_f32(v1 << 16) * inv);
+        return o;
     }
     o.packed = v0 | (v1 << 16);
     return o;
@@ -106,18 +145,24 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-template <int COMP>
+// `vals`: bf16 [M,K/2], or one-byte E4M3 codes [M,K/2] when FP8 (then x_scale[0] is the divisor).
+template <int COMP, bool FP8>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     const uint16_t* __restrict__ X, int64_t M, int K, int64_t ldx, float eps,
-    uint16_t* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ meta_km,
-    int64_t Mpad, float* __restrict__ scale, float* __restrict__ rowsums) {
+    void* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ meta_km,
+    int64_t Mpad, float* __restrict__ scale, float* __restrict__ rowsums,
+    const float* __restrict__ x_scale) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     if (row >= M) return;  // whole wave leaves together
     const uint16_t* xr = X + row * ldx;
-    uint16_t* vr = vals + row * (int64_t)(K / 2);
+    uint16_t* vr = static_cast<uint16_t*>(vals) + row * (int64_t)(K / 2);    // bf16 form
+    uint8_t* vr8 = static_cast<uint8_t*>(vals) + row * (int64_t)(K / 2);      // FP8 form
     uint8_t* mr = meta + row * (int64_t)(K / 8);          // only dereferenced when meta != null
-    uint8_t* kmr = meta_km + row * 8;                      // only dereferenced when meta_km != null
+    constexpr int KM_REC = FP8 ? 16 : 8;                   // k-major record: 128 or 64 dense k
+    uint8_t* kmr = meta_km + row * KM_REC;                 // only dereferenced when meta_km != null
+    float inv = 1.0f;
+    if constexpr (FP8) inv = 1.0f / x_scale[0];
     float num = 0.f, den = 0.f;
     // rows of metadata are K/8 bytes: whole 32-bit words only when K is a multiple of 32
     const bool word_meta = (K & 31) == 0;
@@ -132,8 +177,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int k = k0 + u * 512 + lane * 8;
-            const GroupOut g0 = select_group<COMP>(v[u].x, v[u].y, eps);
-            const GroupOut g1 = select_group<COMP>(v[u].z, v[u].w, eps);
+            const GroupOut g0 = select_group<COMP, FP8>(v[u].x, v[u].y, eps, inv);
+            const GroupOut g1 = select_group<COMP, FP8>(v[u].z, v[u].w, eps, inv);
             if constexpr (COMP == RTL_COMP_ROW || COMP == RTL_COMP_TENSOR) {
                 num += g0.num + g1.num;   // zero-filled lanes past K contribute nothing
                 den += g0.den + g1.den;
@@ -143,7 +188,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
             const uint32_t w = b | (quad_bcast<0x55>(b) << 8) | (quad_bcast<0xAA>(b) << 16) |
                                (quad_bcast<0xFF>(b) << 24);
             if (k < K) {
-                *reinterpret_cast<uint2*>(vr + k / 2) = make_uint2(g0.packed, g1.packed);
+                if constexpr (FP8) *reinterpret_cast<uint32_t*>(vr8 + k / 2) = g0.packed | (g1.packed << 16);
+                else *reinterpret_cast<uint2*>(vr + k / 2) = make_uint2(g0.packed, g1.packed);
                 if (meta) {
                     if (word_meta) {
                         if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(mr + k / 8) = w;
@@ -151,9 +197,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
                         mr[k / 8] = (uint8_t)b;
                     }
                 }
-                // k-major twin: the quad's word is half of the row's 8-byte record of block k / 64
-                if (meta_km && (lane & 3) == 0)
-                    *reinterpret_cast<uint32_t*>(kmr + (int64_t)(k >> 6) * Mpad * 8 + ((k >> 5) & 1) * 4) = w;
+                // k-major twin: the quad's word is one 32-k slice of the row's record of its block
+                // (8 bytes per 64 k, or 16 bytes per 128 k with FP8 values)
+                if (meta_km && (lane & 3) == 0) {
+                    if constexpr (FP8)
+                        *reinterpret_cast<uint32_t*>(kmr + (int64_t)(k >> 7) * Mpad * 16 + ((k >> 5) & 3) * 4) = w;
+                    else
+                        *reinterpret_cast<uint32_t*>(kmr + (int64_t)(k >> 6) * Mpad * 8 + ((k >> 5) & 1) * 4) = w;
+                }
             }
         }
     }
@@ -172,9 +223,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
 }
 
 // TENSOR scope: fold the per-row sums in a fixed order (fp64) and emit the single factor.
+// `fused` (nullable) receives the factor times mul[0] (the FP8 activation scale).
 __global__ __launch_bounds__(256) void tensor_scale_kernel(const float* __restrict__ rowsums,
                                                            int64_t M, float eps,
-                                                           float* __restrict__ scale) {
+                                                           float* __restrict__ scale,
+                                                           const float* __restrict__ mul,
+                                                           float* __restrict__ fused) {
     __shared__ double sn[256], sd[256];
     double n = 0.0, d = 0.0;
     for (int64_t r = threadIdx.x; r < M; r += 256) {
@@ -191,7 +245,30 @@ __global__ __launch_bounds__(256) void tensor_scale_kernel(const float* __restri
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) scale[0] = (float)sqrt(sn[0] / (sd[0] + (double)eps));
+    if (threadIdx.x == 0) {
+        const float sc = (float)sqrt(sn[0] / (sd[0] + (double)eps));
+        scale[0] = sc;
+        if (fused) fused[0] = mul[0] * sc;
+    }
+}
+
+// Direct cast bf16 -> E4M3 (weights "directly quantized to FP8"): 8 elements per thread.
+__global__ __launch_bounds__(256) void quantize_fp8_kernel(const uint16_t* __restrict__ W, int64_t rows,
+                                                           int64_t cols8, int64_t ld,
+                                                           uint8_t* __restrict__ Wq, int64_t ldq) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= rows * cols8) return;
+    const int64_t r = t / cols8, c = (t % cols8) * 8;
+    const uint4 v = *reinterpret_cast<const uint4*>(W + r * ld + c);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t lo = e4m3_pair(bits_to_f32(w[2 * h] << 16), bits_to_f32(w[2 * h] & 0xFFFF0000u));
+        const uint32_t hi = e4m3_pair(bits_to_f32(w[2 * h + 1] << 16), bits_to_f32(w[2 * h + 1] & 0xFFFF0000u));
+        o[h] = lo | (hi << 16);
+    }
+    *reinterpret_cast<uint2*>(Wq + r * ldq + c) = make_uint2(o[0], o[1]);
 }
 
 // One thread per (row, 64-k block): rows run fastest so the k-major writes are contiguous.
@@ -215,32 +292,57 @@ hipError_t launch_meta_to_kmajor(const uint8_t* meta, int64_t M, int64_t K, uint
     return hipGetLastError();
 }
 
-hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
-                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* meta_km,
-                                float* scale, float* rowsums, hipStream_t stream) {
+template <bool FP8>
+static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
+                                  float eps, void* vals, uint8_t* meta, uint8_t* meta_km, float* scale,
+                                  float* rowsums, const float* x_scale, float* fused_scale,
+                                  hipStream_t stream) {
     const int64_t Mpad = kmajor_rows(M);
     const dim3 grid((unsigned)((M + kWavesPerBlock - 1) / kWavesPerBlock));
     const dim3 block(kWavesPerBlock * 64);
     switch (comp) {
         case RTL_COMP_NONE:
-            hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_NONE>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
+            hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_NONE, FP8>), grid, block, 0, stream, X, M,
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
             break;
         case RTL_COMP_GROUP:
-            hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_GROUP>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
+            hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_GROUP, FP8>), grid, block, 0, stream, X, M,
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
             break;
         case RTL_COMP_ROW:
-            hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_ROW>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
+            hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_ROW, FP8>), grid, block, 0, stream, X, M,
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
             break;
         case RTL_COMP_TENSOR:
-            hipLaunchKernelGGL(sparsify_pack_kernel<RTL_COMP_TENSOR>, grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums);
+            hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_TENSOR, FP8>), grid, block, 0, stream, X, M,
+                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
             hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps,
-                               scale);
+                               scale, x_scale, fused_scale);
             break;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
+                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* meta_km,
+                                float* scale, float* rowsums, hipStream_t stream) {
+    return launch_pack_any<false>(X, M, K, ldx, comp, eps, vals, meta, meta_km, scale, rowsums, nullptr,
+                                  nullptr, stream);
+}
+
+hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
+                                    float eps, const float* x_scale, uint8_t* vals8, uint8_t* meta,
+                                    uint8_t* meta_km, float* scale, float* rowsums, float* fused_scale,
+                                    hipStream_t stream) {
+    return launch_pack_any<true>(X, M, K, ldx, comp, eps, vals8, meta, meta_km, scale, rowsums, x_scale,
+                                 fused_scale, stream);
+}
+
+hipError_t launch_quantize_fp8(const uint16_t* W, int64_t rows, int64_t cols, int64_t ld, uint8_t* Wq,
+                               int64_t ldq, hipStream_t stream) {
+    const int64_t n = rows * (cols / 8);
+    hipLaunchKernelGGL(quantize_fp8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, W,
+                       rows, cols / 8, ld, Wq, ldq);
     return hipGetLastError();
 }
 

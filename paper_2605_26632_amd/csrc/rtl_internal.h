@@ -13,6 +13,9 @@ namespace rtl {
 // records of a block contiguous over rows: km[(k / 64) * Mpad + m] (8 bytes), Mpad = kmajor_rows(M).
 // A 256-row tile of one block is then a single contiguous 2 KiB run instead of 256 scattered
 // 8-byte pieces, which keeps the L2 -> CU traffic of the GEMM at its algorithmic size.
+// With FP8 kept values (one stage = 128 dense k) the records are 16 bytes per row and 128-k block:
+// km[(k / 128) * Mpad + m] (16 bytes). Either way a row contributes K / 8 bytes, so the buffer size
+// is the same.
 inline int64_t kmajor_rows(int64_t M) { return (M + 255) / 256 * 256; }
 inline size_t kmajor_bytes(int64_t M, int64_t K) { return (size_t)(K / 64) * (size_t)kmajor_rows(M) * 8; }
 
@@ -23,15 +26,28 @@ inline size_t kmajor_bytes(int64_t M, int64_t K) { return (size_t)(K / 64) * (si
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                 float eps, uint16_t* vals, uint8_t* meta, uint8_t* meta_km,
                                 float* scale, float* rowsums, hipStream_t stream);
+// FP8 form (implementation details, "orthogonal validation with FP8 quantization"): kept values
+// leave as E4M3 codes of (s * x) / x_scale[0] (vals8 [M,K/2] bytes); `meta_km` then uses the 16-byte
+// records (needs K % 128 == 0). `fused_scale` (nullable, [1]) receives x_scale[0] times the TENSOR
+// factor (TENSOR scope only), the single multiplier the GEMM epilogue then needs.
+hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
+                                    float eps, const float* x_scale, uint8_t* vals8, uint8_t* meta,
+                                    uint8_t* meta_km, float* scale, float* rowsums, float* fused_scale,
+                                    hipStream_t stream);
+// Direct cast of a bf16 matrix to E4M3 codes (round to nearest even, saturating), cols % 8 == 0.
+hipError_t launch_quantize_fp8(const uint16_t* W, int64_t rows, int64_t cols, int64_t ld, uint8_t* Wq,
+                               int64_t ldq, hipStream_t stream);
 // canonical -> k-major copy of the metadata (K % 64 == 0).
 hipError_t launch_meta_to_kmajor(const uint8_t* meta, int64_t M, int64_t K, uint8_t* meta_km,
                                  hipStream_t stream);
 
 // ---- GEMMs (gemm.hip) -----------------------------------------------------------------------
 struct GemmArgs {
-    const uint16_t* A;      // dense: X [M,K] (lda); sparse: vals [M,K/2] (lda = K/2)
+    // A and W are bf16 unless fp8 is set (sparse only): then both hold one-byte E4M3 codes and
+    // lda / ldw still count elements.
+    const void* A;          // dense: X [M,K] (lda); sparse: vals [M,K/2] (lda = K/2)
     const uint8_t* meta;    // sparse only: k-major records, kmajor_rows(M) rows per block
-    const uint16_t* W;      // [N,K] (ldw)
+    const void* W;          // [N,K] (ldw)
     const uint16_t* bias;   // nullable [N]
     const float* row_scale; // nullable [M]
     const float* tensor_scale; // nullable [1]
@@ -43,6 +59,7 @@ struct GemmArgs {
     const uint16_t* LA;     // L_A bf16 [N,64] (ldla)
     int64_t ldla;
     int splits;             // split contraction: number of K ranges (grid.y)
+    bool fp8;               // sparse only: E4M3 operands, K % 128 == 0, 16-byte metadata records
 };
 size_t gemm_workspace_bytes(bool sparse, int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream);

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "rtlynx.h")).read()
-    declared = set(re.findall(r"\b(rtl_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(rtl_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(rtl.SYMBOLS), declared ^ set(rtl.SYMBOLS)
     L = rtl.lib()
     for name in declared:
@@ -87,3 +87,39 @@ def test_linear_entry_points_reject_bad_arguments():
 
     assert packed(meta=None) == 1 and packed(vals=None) == 1 and packed(K=96) == 2
     assert packed(meta=FAKE + 4) == 3 and packed(M=0) == 0
+
+
+def test_fp8_entry_points_reject_bad_arguments():
+    L = rtl.lib()
+
+    def quant(W=FAKE, rows=4, cols=64, ld=64, Wq=FAKE, ldq=64):
+        return L.rtl_quantize_fp8(W, rows, cols, ld, Wq, ldq, None)
+
+    assert quant(cols=12) == 2 and quant(ld=32) == 2 and quant(ldq=32) == 2 and quant(rows=-1) == 2
+    assert quant(W=None) == 1 and quant(Wq=None) == 1
+    assert quant(W=FAKE + 2) == 3 and quant(Wq=FAKE + 4) == 3 and quant(ld=68) == 3
+    assert quant(rows=0) == 0
+
+    def pack(X=FAKE, M=4, K=64, ldx=64, comp=1, eps=1e-8, xs=FAKE, vals=FAKE, meta=FAKE, scale=None,
+             ws=None, wsb=0):
+        return L.rtl_sparsify_pack_fp8(X, M, K, ldx, comp, eps, xs, vals, meta, scale, ws, wsb, None)
+
+    assert pack(K=12) == 2 and pack(ldx=32) == 2
+    assert pack(xs=None) == 1 and pack(vals=None) == 1 and pack(comp=2) == 1
+    assert pack(vals=FAKE + 2) == 3 and pack(xs=FAKE + 2) == 3
+    assert pack(comp=5) == 5 and pack(eps=-1.0) == 5
+    assert pack(comp=3, scale=FAKE) == 4
+    assert pack(M=0) == 0
+
+    def lin(X=FAKE, Wq=FAKE, xs=FAKE, Y=FAKE, M=4, N=4, K=128, ldx=128, ldw=128, ldy=4, comp=1, eps=1e-8,
+            ws=FAKE, wsb=1 << 30):
+        return L.rtl_sparse_linear_fp8(X, Wq, xs, None, Y, M, N, K, ldx, ldw, ldy, comp, eps, ws, wsb, None)
+
+    assert lin(K=64, ldx=64, ldw=64) == 2 and lin(ldw=64) == 2 and lin(ldy=2) == 2
+    assert lin(X=None) == 1 and lin(Wq=None) == 1 and lin(xs=None) == 1
+    assert lin(ldw=136) == 3 and lin(Wq=FAKE + 8) == 3
+    assert lin(comp=4) == 5
+    assert lin(ws=None) == 4 and lin(wsb=8) == 4
+    assert lin(M=0) == 0
+    # half the value bytes of the bf16 workspace, same metadata
+    assert L.rtl_sparse_linear_fp8_workspace(4096, 3072, 12288, 1) < L.rtl_sparse_linear_workspace(4096, 3072, 12288, 1)

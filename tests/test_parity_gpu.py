@@ -319,3 +319,148 @@ def test_other_model_layer_shapes(name):
     sel = torch.from_numpy(rows).to(DEV)
     ref = oracle.sparse_linear_oracle(synth.bits(X[sel]), synth.bits(W), scope=oracle.GROUP)["Y"]
     check_y(Y[sel], ref)
+
+
+# ---------------------------------------------------------------- FP8 (E4M3) composition
+def fp8_scale(X):
+    """Symmetric per-tensor activation scale: sqrt(2) * max|x| / 448 bounds every compensated value."""
+    return (X.float().abs().max() * (2.0 ** 0.5) / 448.0).reshape(1).to(torch.float32)
+
+
+def check_y_fp8(Y, r, Wq_np, factor, rows=None):
+    """Output check of the FP8 linear. The benchmark spec's bound (max error 1e-2 of max|Y|) plus an
+    elementwise bound from the arithmetic: one bf16 rounding of the result (2^-8 |ref| allowed) and
+    the accumulation error of the FP8 matrix instruction, which adds the exact 8-bit products of a
+    64-k block with a truncating alignment: measured at most 2^-14 of sum_k |q w| (the bf16
+    instruction shows none); 2^-12 is allowed."""
+    y = y_to_np(Y)
+    ref = r["Y"]
+    assert np.isfinite(y).all()
+    assert rel_max_err(y, ref) <= Y_TOL
+    mag = oracle.linear_f32w(np.abs(oracle.e4m3_decode(r["Q"])), np.abs(oracle.e4m3_decode(Wq_np)))
+    mag = np.abs(np.asarray(factor, dtype=np.float32)) * mag
+    bound = 2.0 ** -8 * np.abs(ref) + 2.0 ** -12 * mag + 1e-30
+    worst = float((np.abs(y.astype(np.float64) - ref) / bound).max())
+    assert worst <= 1.0, worst
+
+
+def test_quantize_fp8_every_bf16_pattern():
+    pats = torch.arange(65536, dtype=torch.int32, device=DEV).to(torch.int16).view(torch.bfloat16).reshape(256, 256)
+    q = rtl.quantize_fp8(pats)
+    torch.cuda.synchronize()
+    ref = oracle.quantize_weights_fp8(synth.bits(pats))
+    assert np.array_equal(q.cpu().numpy(), ref)
+    # strided source and destination, ragged row count
+    W = synth.weights(37, 200, seed=3, device=DEV)
+    big = torch.zeros((37, 264), dtype=torch.bfloat16, device=DEV)
+    big[:, :200] = W
+    out = torch.full((37, 208), 0xAA, dtype=torch.uint8, device=DEV)
+    rtl.quantize_fp8(big[:, :200], out=out[:, :200])
+    torch.cuda.synchronize()
+    assert np.array_equal(out[:, :200].cpu().numpy(), oracle.quantize_weights_fp8(synth.bits(W)))
+    assert (out[:, 200:] == 0xAA).all()
+
+
+def check_pack_fp8(X, comp, xs, eps=1e-8):
+    vals, meta, scale = rtl.sparsify_pack_fp8(X, xs, comp=comp, eps=eps)
+    torch.cuda.synchronize()
+    ref = oracle.sparsify_pack_fp8_oracle(synth.bits(X), float(xs.item()), scope=comp, eps=eps)
+    assert np.array_equal(meta.cpu().numpy(), ref["meta"]), "metadata differs"
+    got = vals.cpu().numpy()
+    bad = np.argwhere(got != ref["vals"])
+    assert len(bad) == 0, (len(bad), bad[:4], got[tuple(bad[0])], ref["vals"][tuple(bad[0])])
+    if comp in (rtl.COMP_ROW, rtl.COMP_TENSOR):
+        assert np.allclose(scale.cpu().numpy(), ref["s"], rtol=2e-6, atol=1e-12)
+    return ref
+
+
+@pytest.mark.parametrize("comp", COMPS)
+def test_pack_fp8_tiny_config(comp):
+    X, _ = synth.workload("tiny", seed=0, device=DEV)
+    check_pack_fp8(X, comp, fp8_scale(X))
+
+
+@pytest.mark.parametrize("M,K", [(1, 8), (3, 24), (7, 520), (65, 1544), (130, 4096)])
+def test_pack_fp8_ragged_shapes_and_scales(M, K):
+    X = synth.activations("laplace", M, K, seed=M * 7 + K, device=DEV)
+    for xs in (fp8_scale(X), fp8_scale(X) * 37.0, fp8_scale(X) / 50.0):    # wide range, subnormal codes, saturation
+        check_pack_fp8(X, rtl.COMP_GROUP, xs)
+        check_pack_fp8(X, rtl.COMP_NONE, xs)
+
+
+def test_pack_fp8_special_values():
+    vals = [0.0, -0.0, 1.0, -1.0, float("inf"), -float("inf"), float("nan"), 1e-30, 3e38, 2.0 ** -9, 448.0, -449.0]
+    rng = np.random.default_rng(1)
+    X = torch.tensor(rng.choice(vals, size=(64, 256)), dtype=torch.float32).to(torch.bfloat16).to(DEV)
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    for comp in (rtl.COMP_NONE, rtl.COMP_GROUP):
+        check_pack_fp8(X, comp, one)
+
+
+def test_pack_fp8_full_size_mlp_down():
+    X, _ = synth.workload("mlp_down", seed=0, device=DEV)
+    check_pack_fp8(X, rtl.COMP_GROUP, fp8_scale(X))
+
+
+@pytest.mark.parametrize("comp", COMPS)
+def test_sparse_linear_fp8_tiny_config(comp):
+    X, W = synth.workload("tiny", seed=0, device=DEV)
+    bias = synth.bias(W.shape[0], seed=5, device=DEV)
+    xs = fp8_scale(X)
+    Wq = rtl.quantize_fp8(W)
+    Y = rtl.sparse_linear_fp8(X, Wq, xs, bias=bias, comp=comp)
+    torch.cuda.synchronize()
+    r = oracle.sparse_linear_fp8_oracle(synth.bits(X), Wq.cpu().numpy(), float(xs.item()),
+                                        bias=synth.bits(bias), scope=comp)
+    f = np.float32(xs.item())
+    if comp == rtl.COMP_ROW:
+        f = f * r["s"][:, None]
+    elif comp == rtl.COMP_TENSOR:
+        f = f * r["s"][0]
+    check_y_fp8(Y, r, Wq.cpu().numpy(), f)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 128), (33, 257, 384), (300, 200, 128), (513, 96, 256), (257, 449, 640)])
+def test_sparse_linear_fp8_ragged(M, N, K):
+    X = synth.activations("laplace", M, K, seed=M + N, device=DEV)
+    W = synth.weights(N, K, seed=K, device=DEV)
+    xs = fp8_scale(X)
+    Wq = rtl.quantize_fp8(W)
+    out = torch.full((M, N + 3), 7.0, dtype=torch.bfloat16, device=DEV)
+    rtl.sparse_linear_fp8(X, Wq, xs, comp=rtl.COMP_GROUP, out=out[:, :N])
+    torch.cuda.synchronize()
+    r = oracle.sparse_linear_fp8_oracle(synth.bits(X), Wq.cpu().numpy(), float(xs.item()), scope=oracle.GROUP)
+    check_y_fp8(out[:, :N], r, Wq.cpu().numpy(), xs.item())
+    assert (out[:, N:] == 7.0).all()
+
+
+def test_sparse_linear_fp8_small_integers_are_exact():
+    g = torch.Generator(device="cpu").manual_seed(3)
+    M, N, K = 96, 160, 512
+    Xi = torch.randint(1, 9, (M, K), generator=g) * (torch.randint(0, 2, (M, K), generator=g) * 2 - 1)
+    Xi.view(M, K // 4, 4)[:, :, 1] = 0          # exactly 2:4 sparse at varying positions
+    Xi.view(M, K // 4, 4)[:, :, 3] = 0
+    Wi = torch.randint(-8, 9, (N, K), generator=g)
+    X = Xi.to(torch.bfloat16).to(DEV)
+    Wq = rtl.quantize_fp8(Wi.to(torch.bfloat16).to(DEV))
+    one = torch.ones(1, dtype=torch.float32, device=DEV)
+    Y = rtl.sparse_linear_fp8(X, Wq, one, comp=rtl.COMP_NONE)
+    torch.cuda.synchronize()
+    exact = (Xi.double() @ Wi.double().T)
+    assert exact.abs().max() < 2 ** 15
+    # the integer result is exact in fp32; only the bf16 store rounds it
+    assert torch.equal(Y.cpu(), exact.float().to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("name", ["mlp_down", "fc1", "out_proj", "hr_qkv"])
+def test_sparse_linear_fp8_full_size_sampled_rows(name):
+    X, W = synth.workload(name, seed=1, device=DEV)
+    M = X.shape[0]
+    xs = fp8_scale(X)
+    Wq = rtl.quantize_fp8(W)
+    Y = rtl.sparse_linear_fp8(X, Wq, xs, comp=rtl.COMP_GROUP)
+    torch.cuda.synchronize()
+    rows = sampled_rows(M, 8, seed=13)
+    sel = torch.from_numpy(rows).to(DEV)
+    r = oracle.sparse_linear_fp8_oracle(synth.bits(X[sel]), Wq.cpu().numpy(), float(xs.item()), scope=oracle.GROUP)
+    check_y_fp8(Y[sel], r, Wq.cpu().numpy(), xs.item())
