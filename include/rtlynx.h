@@ -14,7 +14,8 @@
  *    strides in ELEMENTS. Inputs are never modified; outputs are fully overwritten.
  *  - All argument checks happen before any launch, so error paths touch no memory:
  *      RTL_ERR_NULL       a required pointer is NULL
- *      RTL_ERR_SHAPE      negative size, K not a multiple of the required granule, ld < extent
+ *      RTL_ERR_SHAPE      negative size, K not a multiple of the required granule, ld < extent,
+ *                         M, N or K above 2^30, or a row stride of a GEMM operand above 2^22 elements
  *      RTL_ERR_ALIGN      a pointer or a row stride breaks the stated alignment
  *      RTL_ERR_WORKSPACE  workspace NULL or smaller than the matching *_workspace() query
  *      RTL_ERR_ARG        an enum value out of range, or eps negative / not finite

@@ -80,6 +80,8 @@ static rtl_status check_linear(const void* A, const void* W, const void* Y, int6
         return RTL_ERR_SHAPE;
     if (M > ((int64_t)1 << 30) || N > ((int64_t)1 << 30) || K > ((int64_t)1 << 30))
         return RTL_ERR_SHAPE;
+    // the tile loop addresses the 256 rows of a tile with 32-bit byte offsets from the tile's base
+    if (lda > ((int64_t)1 << 22) || ldw > ((int64_t)1 << 22)) return RTL_ERR_SHAPE;
     if (M == 0 || N == 0) return RTL_OK;
     if (!A || !W || !Y) return RTL_ERR_NULL;
     if (lda % 8 != 0 || ldw % ldw_granule != 0 || !aligned(A, 16) || !aligned(W, 16) || !aligned(Y, 2))
