@@ -168,9 +168,15 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     constexpr int MREC = L::kMetaRec;                 // metadata bytes per row and stage
     constexpr int IXW = FP8 ? 2 : 1;                  // metadata words a lane holds per stage and row block
     // one wave-wide direct-to-LDS load moves 64 chunks of 16 bytes = 1 KiB
-    constexpr int A_LOADS = L::kABytes / 1024, B_LOADS = L::kBBytes / 1024;
-    static_assert(A_LOADS % NW == 0 && B_LOADS % NW == 0, "tile loads must divide over the waves");
-    constexpr int A_PER_W = A_LOADS / NW, B_PER_W = B_LOADS / NW;
+    constexpr int A_LOADS = L::kABytes / 1024;
+    static_assert(A_LOADS % NW == 0, "tile loads must divide over the waves");
+    // The B tile is dealt to the waves in runs of B_CH 16-byte chunks. When that is an odd
+    // multiple of 32 (192-row dense tile: 96 chunks), a wave's last load runs with its upper half
+    // masked off, so every wave still issues the same number of loads.
+    constexpr int B_CH = L::kBBytes / 16 / NW;
+    static_assert((L::kBBytes / 16) % NW == 0 && B_CH % 32 == 0, "B tile must divide over the waves");
+    constexpr int A_PER_W = A_LOADS / NW, B_PER_W = (B_CH + 63) / 64;
+    constexpr bool B_HALF = (B_CH % 64) != 0;
     constexpr int M_LOADS = SPARSE ? (BM * MREC) / 256 : 0;  // metadata: 4 bytes per lane per load
     static_assert(!SPARSE || M_LOADS % NW == 0, "metadata loads must divide over the waves");
     constexpr int M_PER_W = M_LOADS / NW;
@@ -219,7 +225,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     uint32_t ob[B_PER_W];
 #pragma unroll
     for (int s = 0; s < B_PER_W; ++s) {
-        const int p = (wave * B_PER_W + s) * 64 + lane;
+        const int p = wave * B_CH + min(s * 64 + lane, B_CH - 1);   // masked lanes of a half load: any valid chunk
         int row, c;
         if constexpr (SPARSE) unswz8(p, row, c); else unswz4(p, row, c);
         const int64_t gr = min((int64_t)row, rows_b - 1);
@@ -246,8 +252,12 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
             lds_dma16_so(base_a + (int64_t)kt * (A_ELEMS * ESZ), oa[n], base + (wave * A_PER_W + n) * 1024);
         } else if constexpr (n < A_PER_W + B_PER_W) {
             constexpr int s = n - A_PER_W;
-            lds_dma16_so(base_b + (int64_t)kt * (KSTAGE * ESZ), ob[s],
-                         base + L::kABytes + L::kMetaBytes + (wave * B_PER_W + s) * 1024);
+            const uint32_t dst = base + L::kABytes + L::kMetaBytes + (wave * B_CH + s * 64) * 16;
+            if constexpr (B_HALF && s == B_PER_W - 1) {
+                if (lane < 32) lds_dma16_so(base_b + (int64_t)kt * (KSTAGE * ESZ), ob[s], dst);
+            } else {
+                lds_dma16_so(base_b + (int64_t)kt * (KSTAGE * ESZ), ob[s], dst);
+            }
         } else if constexpr (SPARSE && n < A_PER_W + B_PER_W + M_PER_W) {
             constexpr int s = n - A_PER_W - B_PER_W;
             lds_dma4_so(base_m + (int64_t)kt * meta_stride + s * 256, om,
@@ -707,11 +717,12 @@ size_t gemm_workspace_bytes(bool, int64_t, int64_t, int64_t) { return 0; }
 // operand stages out of L2, so a tile costs about (bytes per stage) and a launch costs
 // ceil(tiles / CUs) rounds of that: 256x256 moves 51 KB per stage, 256x192 moves 43 KB but
 // yields a third more tiles, which pays when it turns a 3/4-full round into a full one.
-static bool prefer_192(int64_t M, int64_t N) {
+// (The dense kernel moves 32 and 28 KB per stage of half the depth.)
+static bool prefer_192(int64_t M, int64_t N, int64_t kb256 = 51, int64_t kb192 = 43) {
     constexpr int64_t kCUs = 256;
     const int64_t tm = (M + 255) / 256;
     const int64_t t256 = tm * ((N + 255) / 256), t192 = tm * ((N + 191) / 192);
-    const int64_t c256 = (t256 + kCUs - 1) / kCUs * 51, c192 = (t192 + kCUs - 1) / kCUs * 43;
+    const int64_t c256 = (t256 + kCUs - 1) / kCUs * kb256, c192 = (t192 + kCUs - 1) / kCUs * kb192;
     return c192 < c256;
 }
 
@@ -729,6 +740,7 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
         if (lora) return launch_cfg<true, 256, 256, 2, 4, 3, 1>(a, stream);
         return launch_cfg<true, 256, 256, 2, 4, 3>(a, stream);
     }
+    if (prefer_192(a.M, a.N, 32, 28)) return launch_cfg<false, 256, 192, 4, 2, 3>(a, stream);
     return launch_cfg<false, 256, 256, 2, 4, 3>(a, stream);
 }
 
