@@ -18,7 +18,7 @@ struct SparseWs {
 SparseWs sparse_ws(int64_t M, int64_t N, int64_t K, rtl_comp comp, size_t val_bytes = 2) {
     SparseWs w{};
     size_t off = 0;
-    w.vals = off; off += round_up((size_t)M * (size_t)(K / 2) * val_bytes, 256);
+    w.vals = off; off += round_up(rtl::kmajor_val_bytes(M, K, val_bytes), 256);
     w.meta = off; off += round_up(rtl::kmajor_bytes(M, K), 256);
     w.scale = off; off += round_up((size_t)((M > 0 ? M : 1) + 1) * sizeof(float), 256);   // + one fused scalar
     w.pack = off; off += round_up(rtl_sparsify_pack_workspace(M, K, comp), 256);
@@ -68,7 +68,7 @@ rtl_status rtl_sparsify_pack(const void* X, int64_t M, int64_t K, int64_t ldx, r
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
     hipError_t e = rtl::launch_sparsify_pack(
         static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, static_cast<uint16_t*>(vals),
-        static_cast<uint8_t*>(meta), nullptr, scale, static_cast<float*>(workspace),
+        static_cast<uint8_t*>(meta), nullptr, nullptr, scale, static_cast<float*>(workspace),
         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
@@ -89,10 +89,11 @@ static rtl_status check_linear(const void* A, const void* W, const void* Y, int6
     return RTL_OK;
 }
 
-// rtl_packed_linear workspace: [k-major copy of the metadata | gemm scratch]
+// rtl_packed_linear workspace: [k-major copy of the values | k-major copy of the metadata | gemm scratch]
 size_t rtl_packed_linear_workspace(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    return round_up(rtl::kmajor_bytes(M, K), 256) + rtl::gemm_workspace_bytes(true, M, N, K);
+    return round_up(rtl::kmajor_val_bytes(M, K, 2), 256) + round_up(rtl::kmajor_bytes(M, K), 256) +
+           rtl::gemm_workspace_bytes(true, M, N, K);
 }
 
 rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* row_scale,
@@ -107,11 +108,13 @@ rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* ro
     if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
     rtl::GemmArgs g{};
-    g.A = vals;
-    uint8_t* km = static_cast<uint8_t*>(workspace);
-    hipError_t e = rtl::launch_meta_to_kmajor(static_cast<const uint8_t*>(meta), M, K, km,
-                                              static_cast<hipStream_t>(stream));
+    uint8_t* vkm = static_cast<uint8_t*>(workspace);
+    uint8_t* km = vkm + round_up(rtl::kmajor_val_bytes(M, K, 2), 256);
+    hipError_t e = rtl::launch_operand_to_kmajor(static_cast<const uint16_t*>(vals),
+                                                 static_cast<const uint8_t*>(meta), M, K, vkm, km,
+                                                 static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return RTL_ERR_HIP;
+    g.A = vkm;
     g.meta = km;
     g.W = W;
     g.bias = static_cast<const uint16_t*>(bias);
@@ -119,7 +122,7 @@ rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* ro
     g.tensor_scale = tensor_scale;
     g.Y = static_cast<uint16_t*>(Y);
     g.partials = reinterpret_cast<float*>(km + round_up(rtl::kmajor_bytes(M, K), 256));
-    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
+    g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
@@ -144,9 +147,8 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
     float* scale = reinterpret_cast<float*>(base + ws.scale);
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = rtl::launch_sparsify_pack(
-        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
-        reinterpret_cast<uint16_t*>(base + ws.vals), nullptr, base + ws.meta, scale,
-        reinterpret_cast<float*>(base + ws.pack), s);
+        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr, base + ws.vals,
+        base + ws.meta, scale, reinterpret_cast<float*>(base + ws.pack), s);
     if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};
     g.A = base + ws.vals;
@@ -157,7 +159,7 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
     g.tensor_scale = comp == RTL_COMP_TENSOR ? scale : nullptr;
     g.Y = static_cast<uint16_t*>(Y);
     g.partials = reinterpret_cast<float*>(base + ws.gemm);
-    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
+    g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, s);
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
@@ -195,9 +197,9 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
                                          static_cast<const uint16_t*>(LB), ldlb, M, K,
                                          reinterpret_cast<float*>(base + p_off), T, s);
     if (e != hipSuccess) return RTL_ERR_HIP;
-    e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
-                                  reinterpret_cast<uint16_t*>(base + ws.vals), nullptr, base + ws.meta,
-                                  scale, reinterpret_cast<float*>(base + ws.pack), s);
+    e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr,
+                                  base + ws.vals, base + ws.meta, scale,
+                                  reinterpret_cast<float*>(base + ws.pack), s);
     if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};
     g.A = base + ws.vals;
@@ -207,7 +209,7 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
     g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
     g.tensor_scale = comp == RTL_COMP_TENSOR ? scale : nullptr;
     g.Y = static_cast<uint16_t*>(Y);
-    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
+    g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     g.T = T;
     g.LA = static_cast<const uint16_t*>(LA);
     g.ldla = ldla;
@@ -250,7 +252,7 @@ rtl_status rtl_sparsify_pack_fp8(const void* X, int64_t M, int64_t K, int64_t ld
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
     hipError_t e = rtl::launch_sparsify_pack_fp8(
         static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, x_scale, static_cast<uint8_t*>(vals),
-        static_cast<uint8_t*>(meta), nullptr, scale, static_cast<float*>(workspace), nullptr,
+        static_cast<uint8_t*>(meta), nullptr, nullptr, scale, static_cast<float*>(workspace), nullptr,
         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
@@ -277,7 +279,7 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
     float* fused = scale + (comp == RTL_COMP_ROW ? M : 1);   // x_scale times the TENSOR factor
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = rtl::launch_sparsify_pack_fp8(
-        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, x_scale, base + ws.vals, nullptr,
+        static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, x_scale, nullptr, nullptr, base + ws.vals,
         base + ws.meta, scale, reinterpret_cast<float*>(base + ws.pack), fused, s);
     if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};
@@ -290,7 +292,7 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
     g.tensor_scale = comp == RTL_COMP_TENSOR ? fused : x_scale;   // dequantisation rides on the epilogue
     g.Y = static_cast<uint16_t*>(Y);
     g.partials = reinterpret_cast<float*>(base + ws.gemm);
-    g.M = M; g.N = N; g.K = K; g.lda = K / 2; g.ldw = ldw; g.ldy = ldy;
+    g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, s);
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }

@@ -210,7 +210,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     // ---- global -> LDS: every lane owns fixed chunks; rows past the edge are clamped to the last
     //      valid row (their products only reach outputs that are never stored) -----------------
     // wave-uniform bases of this tile's three streams, already advanced to the first stage
-    const uint8_t* base_a = static_cast<const uint8_t*>(a.A) + (m0 * a.lda + (int64_t)kt_first * A_ELEMS) * ESZ;
+    // Sparse A is the k-major value buffer: 64 bytes per row and stage, the rows of a stage
+    // contiguous, so the tile's stage is one 16 KiB run; dense A is row-major X.
+    const int64_t rows_pad = (a.M + 255) / 256 * 256;
+    const int64_t a_stride = SPARSE ? rows_pad * 64 : (int64_t)(A_ELEMS * ESZ);   // bytes between stages
+    const uint8_t* base_a = SPARSE
+        ? static_cast<const uint8_t*>(a.A) + m0 * 64 + (int64_t)kt_first * a_stride
+        : static_cast<const uint8_t*>(a.A) + (m0 * a.lda + (int64_t)kt_first * A_ELEMS) * ESZ;
     const uint8_t* base_b = static_cast<const uint8_t*>(a.W) + (n0 * a.ldw + (int64_t)kt_first * KSTAGE) * ESZ;
     const int64_t rows_a = a.M - m0, rows_b = a.N - n0;     // valid rows from the tile's first row
     uint32_t oa[A_PER_W];
@@ -220,7 +226,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         int row, c;
         unswz4(p, row, c);
         const int64_t gr = min((int64_t)row, rows_a - 1);
-        oa[s] = (uint32_t)(gr * a.lda * ESZ + c * 16);
+        // (the k-major buffer is padded to whole tiles: rows past M hold unspecified bytes whose
+        //  products only reach outputs that are never stored)
+        oa[s] = SPARSE ? (uint32_t)(row * 64 + c * 16) : (uint32_t)(gr * a.lda * ESZ + c * 16);
     }
     uint32_t ob[B_PER_W];
 #pragma unroll
@@ -240,7 +248,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         om = (uint32_t)(wave * M_PER_W * 256 + lane * 4);
     }
 
-    const int64_t meta_stride = ((a.M + 255) / 256 * 256) * MREC;   // bytes between stage blocks
+    const int64_t meta_stride = rows_pad * MREC;   // bytes between stage blocks
     // Load number n (0 .. LOADS_PER_STAGE-1) of this wave for stage kt into ring buffer `stage`.
     // The loads of a stage are issued one at a time between matrix instructions: the texture
     // addresser takes a wave-wide 1 KiB request every ~16 cycles and a wave stalls at a request
@@ -249,7 +257,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         constexpr int n = decltype(n_tag)::value;
         const uint32_t base = lds0 + stage * L::kStage;
         if constexpr (n < A_PER_W) {
-            lds_dma16_so(base_a + (int64_t)kt * (A_ELEMS * ESZ), oa[n], base + (wave * A_PER_W + n) * 1024);
+            lds_dma16_so(base_a + (int64_t)kt * a_stride, oa[n], base + (wave * A_PER_W + n) * 1024);
         } else if constexpr (n < A_PER_W + B_PER_W) {
             constexpr int s = n - A_PER_W;
             const uint32_t dst = base + L::kABytes + L::kMetaBytes + (wave * B_CH + s * 64) * 16;

@@ -149,15 +149,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int COMP, bool FP8>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     const uint16_t* __restrict__ X, int64_t M, int K, int64_t ldx, float eps,
-    void* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ meta_km,
-    int64_t Mpad, float* __restrict__ scale, float* __restrict__ rowsums,
-    const float* __restrict__ x_scale) {
+    void* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ vals_km,
+    uint8_t* __restrict__ meta_km, int64_t Mpad, float* __restrict__ scale,
+    float* __restrict__ rowsums, const float* __restrict__ x_scale) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     if (row >= M) return;  // whole wave leaves together
     const uint16_t* xr = X + row * ldx;
-    uint16_t* vr = static_cast<uint16_t*>(vals) + row * (int64_t)(K / 2);    // bf16 form
-    uint8_t* vr8 = static_cast<uint8_t*>(vals) + row * (int64_t)(K / 2);      // FP8 form
+    // canonical value row (only dereferenced when vals != null): bf16 form / FP8 form
+    uint16_t* vr = static_cast<uint16_t*>(vals) + row * (int64_t)(K / 2);
+    uint8_t* vr8 = static_cast<uint8_t*>(vals) + row * (int64_t)(K / 2);
+    uint8_t* vkr = vals_km + row * 64;                     // only dereferenced when vals_km != null
     uint8_t* mr = meta + row * (int64_t)(K / 8);          // only dereferenced when meta != null
     constexpr int KM_REC = FP8 ? 16 : 8;                   // k-major record: 128 or 64 dense k
     uint8_t* kmr = meta_km + row * KM_REC;                 // only dereferenced when meta_km != null
@@ -188,8 +190,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
             const uint32_t w = b | (quad_bcast<0x55>(b) << 8) | (quad_bcast<0xAA>(b) << 16) |
                                (quad_bcast<0xFF>(b) << 24);
             if (k < K) {
-                if constexpr (FP8) *reinterpret_cast<uint32_t*>(vr8 + k / 2) = g0.packed | (g1.packed << 16);
-                else *reinterpret_cast<uint2*>(vr + k / 2) = make_uint2(g0.packed, g1.packed);
+                if constexpr (FP8) {
+                    const uint32_t codes = g0.packed | (g1.packed << 16);
+                    if (vals) *reinterpret_cast<uint32_t*>(vr8 + k / 2) = codes;
+                    // k-major twin: 64 codes (64 bytes) per row and 128-k block
+                    if (vals_km)
+                        *reinterpret_cast<uint32_t*>(vkr + (int64_t)(k >> 7) * Mpad * 64 + ((k & 127) >> 1)) = codes;
+                } else {
+                    const uint2 pair = make_uint2(g0.packed, g1.packed);
+                    if (vals) *reinterpret_cast<uint2*>(vr + k / 2) = pair;
+                    // k-major twin: 32 values (64 bytes) per row and 64-k block
+                    if (vals_km)
+                        *reinterpret_cast<uint2*>(vkr + (int64_t)(k >> 6) * Mpad * 64 + (k & 63)) = pair;
+                }
                 if (meta) {
                     if (word_meta) {
                         if ((lane & 3) == 0) *reinterpret_cast<uint32_t*>(mr + k / 8) = w;
@@ -271,31 +284,41 @@ __global__ __launch_bounds__(256) void quantize_fp8_kernel(const uint16_t* __res
     *reinterpret_cast<uint2*>(Wq + r * ldq + c) = make_uint2(o[0], o[1]);
 }
 
-// One thread per (row, 64-k block): rows run fastest so the k-major writes are contiguous.
-__global__ __launch_bounds__(256) void meta_to_kmajor_kernel(const uint8_t* __restrict__ meta,
-                                                             int64_t M, int64_t KB, int64_t Mpad,
-                                                             uint8_t* __restrict__ km) {
+// One thread per (row, 64-k block) and 16-byte piece: rows run fastest so that the k-major writes of
+// a warp are contiguous. Piece 0..3 = the block's 64 bytes of values; piece 0 also moves the
+// 8-byte metadata record.
+__global__ __launch_bounds__(256) void operand_to_kmajor_kernel(const uint16_t* __restrict__ vals,
+                                                                const uint8_t* __restrict__ meta,
+                                                                int64_t M, int64_t KB, int64_t Mpad,
+                                                                uint8_t* __restrict__ vals_km,
+                                                                uint8_t* __restrict__ meta_km) {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= M * KB) return;
-    const int64_t row = t % M, kb = t / M;
-    const uint2 v = *reinterpret_cast<const uint2*>(meta + row * KB * 8 + kb * 8);
-    *reinterpret_cast<uint2*>(km + (kb * Mpad + row) * 8) = v;
+    if (t >= M * KB * 4) return;
+    const int piece = (int)(t & 3);
+    const int64_t row = (t >> 2) % M, kb = (t >> 2) / M;
+    const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint8_t*>(vals) +
+                                                    (row * KB + kb) * 64 + piece * 16);
+    *reinterpret_cast<uint4*>(vals_km + (kb * Mpad + row) * 64 + piece * 16) = v;
+    if (piece == 0) {
+        const uint2 m = *reinterpret_cast<const uint2*>(meta + row * KB * 8 + kb * 8);
+        *reinterpret_cast<uint2*>(meta_km + (kb * Mpad + row) * 8) = m;
+    }
 }
 
 }  // namespace
 
-hipError_t launch_meta_to_kmajor(const uint8_t* meta, int64_t M, int64_t K, uint8_t* meta_km,
-                                 hipStream_t stream) {
-    const int64_t KB = K / 64, n = M * KB;
-    hipLaunchKernelGGL(meta_to_kmajor_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
-                       meta, M, KB, kmajor_rows(M), meta_km);
+hipError_t launch_operand_to_kmajor(const uint16_t* vals, const uint8_t* meta, int64_t M, int64_t K,
+                                    uint8_t* vals_km, uint8_t* meta_km, hipStream_t stream) {
+    const int64_t KB = K / 64, n = M * KB * 4;
+    hipLaunchKernelGGL(operand_to_kmajor_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                       vals, meta, M, KB, kmajor_rows(M), vals_km, meta_km);
     return hipGetLastError();
 }
 
 template <bool FP8>
 static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
-                                  float eps, void* vals, uint8_t* meta, uint8_t* meta_km, float* scale,
-                                  float* rowsums, const float* x_scale, float* fused_scale,
+                                  float eps, void* vals, uint8_t* meta, uint8_t* vals_km, uint8_t* meta_km,
+                                  float* scale, float* rowsums, const float* x_scale, float* fused_scale,
                                   hipStream_t stream) {
     const int64_t Mpad = kmajor_rows(M);
     const dim3 grid((unsigned)((M + kWavesPerBlock - 1) / kWavesPerBlock));
@@ -303,19 +326,19 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
     switch (comp) {
         case RTL_COMP_NONE:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_NONE, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
             break;
         case RTL_COMP_GROUP:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_GROUP, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
             break;
         case RTL_COMP_ROW:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_ROW, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
             break;
         case RTL_COMP_TENSOR:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_TENSOR, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
             hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps,
                                scale, x_scale, fused_scale);
             break;
@@ -324,18 +347,18 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
 }
 
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
-                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* meta_km,
-                                float* scale, float* rowsums, hipStream_t stream) {
-    return launch_pack_any<false>(X, M, K, ldx, comp, eps, vals, meta, meta_km, scale, rowsums, nullptr,
-                                  nullptr, stream);
+                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* vals_km,
+                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream) {
+    return launch_pack_any<false>(X, M, K, ldx, comp, eps, vals, meta, vals_km, meta_km, scale, rowsums,
+                                  nullptr, nullptr, stream);
 }
 
 hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                     float eps, const float* x_scale, uint8_t* vals8, uint8_t* meta,
-                                    uint8_t* meta_km, float* scale, float* rowsums, float* fused_scale,
-                                    hipStream_t stream) {
-    return launch_pack_any<true>(X, M, K, ldx, comp, eps, vals8, meta, meta_km, scale, rowsums, x_scale,
-                                 fused_scale, stream);
+                                    uint8_t* vals_km, uint8_t* meta_km, float* scale, float* rowsums,
+                                    float* fused_scale, hipStream_t stream) {
+    return launch_pack_any<true>(X, M, K, ldx, comp, eps, vals8, meta, vals_km, meta_km, scale, rowsums,
+                                 x_scale, fused_scale, stream);
 }
 
 hipError_t launch_quantize_fp8(const uint16_t* W, int64_t rows, int64_t cols, int64_t ld, uint8_t* Wq,

@@ -16,36 +16,45 @@ namespace rtl {
 // With FP8 kept values (one stage = 128 dense k) the records are 16 bytes per row and 128-k block:
 // km[(k / 128) * Mpad + m] (16 bytes). Either way a row contributes K / 8 bytes, so the buffer size
 // is the same.
+// The kept values the GEMM streams use the same blocking: 64 bytes per row and block (32 bf16 of a
+// 64-k block, or 64 FP8 codes of a 128-k block), vals_km[(block * Mpad + m) * 64]. A 256-row tile of
+// one stage is then one contiguous 16 KiB run of whole 128-byte lines; in the row-major form every
+// row contributes a 64-byte half line per stage and the L2 sees twice the requests for it.
 inline int64_t kmajor_rows(int64_t M) { return (M + 255) / 256 * 256; }
 inline size_t kmajor_bytes(int64_t M, int64_t K) { return (size_t)(K / 64) * (size_t)kmajor_rows(M) * 8; }
+// bytes of the k-major value buffer; val_bytes = 2 (bf16) or 1 (FP8)
+inline size_t kmajor_val_bytes(int64_t M, int64_t K, size_t val_bytes) {
+    return (size_t)kmajor_rows(M) * (size_t)(K / 2) * val_bytes;
+}
 
 // ---- sparsify + pack (pack.hip) -------------------------------------------------------------
-// Launches the select/compensate/compress sweep. `meta` (canonical) and `meta_km` (k-major, needs
-// K % 64 == 0) are each optional; `rowsums` ([M][2] fp32) is only touched for RTL_COMP_TENSOR.
-// Returns the HIP launch status.
+// Launches the select/compensate/compress sweep. The canonical outputs (`vals`, `meta`) and the
+// k-major ones (`vals_km`, `meta_km`, need K % 64 == 0) are each optional; `rowsums` ([M][2] fp32)
+// is only touched for RTL_COMP_TENSOR. Returns the HIP launch status.
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
-                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* meta_km,
-                                float* scale, float* rowsums, hipStream_t stream);
+                                float eps, uint16_t* vals, uint8_t* meta, uint8_t* vals_km,
+                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream);
 // FP8 form (implementation details, "orthogonal validation with FP8 quantization"): kept values
 // leave as E4M3 codes of (s * x) / x_scale[0] (vals8 [M,K/2] bytes); `meta_km` then uses the 16-byte
-// records (needs K % 128 == 0). `fused_scale` (nullable, [1]) receives x_scale[0] times the TENSOR
-// factor (TENSOR scope only), the single multiplier the GEMM epilogue then needs.
+// records and `vals_km` 128-k blocks (need K % 128 == 0). `fused_scale` (nullable, [1]) receives
+// x_scale[0] times the TENSOR factor (TENSOR scope only), the single multiplier the GEMM epilogue
+// then needs.
 hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                     float eps, const float* x_scale, uint8_t* vals8, uint8_t* meta,
-                                    uint8_t* meta_km, float* scale, float* rowsums, float* fused_scale,
-                                    hipStream_t stream);
+                                    uint8_t* vals_km, uint8_t* meta_km, float* scale, float* rowsums,
+                                    float* fused_scale, hipStream_t stream);
 // Direct cast of a bf16 matrix to E4M3 codes (round to nearest even, saturating), cols % 8 == 0.
 hipError_t launch_quantize_fp8(const uint16_t* W, int64_t rows, int64_t cols, int64_t ld, uint8_t* Wq,
                                int64_t ldq, hipStream_t stream);
-// canonical -> k-major copy of the metadata (K % 64 == 0).
-hipError_t launch_meta_to_kmajor(const uint8_t* meta, int64_t M, int64_t K, uint8_t* meta_km,
-                                 hipStream_t stream);
+// canonical -> k-major copy of the compressed bf16 operand (values and metadata, K % 64 == 0).
+hipError_t launch_operand_to_kmajor(const uint16_t* vals, const uint8_t* meta, int64_t M, int64_t K,
+                                    uint8_t* vals_km, uint8_t* meta_km, hipStream_t stream);
 
 // ---- GEMMs (gemm.hip) -----------------------------------------------------------------------
 struct GemmArgs {
     // A and W are bf16 unless fp8 is set (sparse only): then both hold one-byte E4M3 codes and
     // lda / ldw still count elements.
-    const void* A;          // dense: X [M,K] (lda); sparse: vals [M,K/2] (lda = K/2)
+    const void* A;          // dense: X [M,K] (lda); sparse: k-major kept values (lda unused)
     const uint8_t* meta;    // sparse only: k-major records, kmajor_rows(M) rows per block
     const void* W;          // [N,K] (ldw)
     const uint16_t* bias;   // nullable [N]
