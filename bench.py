@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per sparse-GEMM launch on the default workload, from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_kernel_sparse_mlp_down.md
 # (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 KiB after calibration against a plain 1 GiB copy).
-GEMM_TRAFFIC_BYTES = {"mlp_down": int((186033 * 2.0 + 24576 * 1.0) * 1024)}
+GEMM_TRAFFIC_BYTES = {"mlp_down": int((184788 * 2.0 + 24576 * 1.0) * 1024)}
 
 
 X_KIND = {"gelu": "post-GELU", "laplace": "Laplace rows x log-normal channel scales",
@@ -100,10 +100,19 @@ def run_sweep(args, torch, rtl, synth, dev, comp):
         for kind, x, w in layers:
             torch.matmul(x, w.t(), out=outs[kind])
 
+    # FP8 composition of the same sweep: weights cast once, one calibrated activation scale per layer
+    wq = [rtl.quantize_fp8(w) for _, _, w in layers]
+    xs = [(x.float().abs().max() * (2.0 ** 0.5) / 448.0).reshape(1).to(torch.float32) for _, x, _ in layers]
+
+    def fp8_pass():
+        for (kind, x, _), q, sc in zip(layers, wq, xs):
+            rtl.sparse_linear_fp8(x, q, sc, comp=comp, out=outs[kind], ws=ws)
+
     steps, warmup = min(args.steps, 10), min(args.warmup, 2)
     ms_sparse = timed(sparse_pass, steps, warmup)
     ms_dense = timed(dense_pass, steps, warmup)
     ms_blas = timed(blas_pass, steps, warmup)
+    ms_fp8 = timed(fp8_pass, steps, warmup)
     print(json.dumps({
         "metric": "effective TFLOP/s + speedup vs dense bf16 GEMM at DiT linear shapes (M=4096)",
         "value": round(flops / (ms_sparse * 1e-3) / 1e12, 1), "unit": "TFLOP/s", "n_gpus": 1,
@@ -114,6 +123,7 @@ def run_sweep(args, torch, rtl, synth, dev, comp):
         "dense_linear_ms": round(ms_dense, 3), "hipblaslt_dense_ms": round(ms_blas, 3),
         "speedup_vs_dense_linear": round(ms_dense / ms_sparse, 3),
         "speedup_vs_hipblaslt_dense": round(ms_blas / ms_sparse, 3),
+        "with_fp8_e4m3": {"ms_per_step": round(ms_fp8, 3), "tflops": round(flops / (ms_fp8 * 1e-3) / 1e12, 1)},
         "roofline": None, "cpu_baseline": None}))
 
 

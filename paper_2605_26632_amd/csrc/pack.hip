@@ -7,7 +7,9 @@
 // Mapping: one wavefront per row; a lane takes 8 consecutive bf16 (one 16-byte load = two
 // groups) per step and the wave walks the row in steps of 512 elements, so every load, the
 // 8-byte value stores and the 4-byte metadata stores (four lanes' bytes gathered with DPP
-// quad permutes) are contiguous across the wave.
+// quad permutes) are contiguous across the wave in the canonical (row-major) output. The
+// k-major output the GEMM streams (64-byte value blocks and 8-byte metadata records per row and
+// 64-k block, rows contiguous) is written as 64-byte pieces, two neighbouring rows per line.
 #include "rtl_internal.h"
 
 namespace rtl {
