@@ -464,3 +464,23 @@ def test_sparse_linear_fp8_full_size_sampled_rows(name):
     sel = torch.from_numpy(rows).to(DEV)
     r = oracle.sparse_linear_fp8_oracle(synth.bits(X[sel]), Wq.cpu().numpy(), float(xs.item()), scope=oracle.GROUP)
     check_y_fp8(Y[sel], r, Wq.cpu().numpy(), xs.item())
+
+
+@pytest.mark.parametrize("M,N,K", [(100003, 40, 64), (40, 70001, 64), (2051, 2051, 64)])
+def test_large_grids_small_contraction(M, N, K):
+    """Many tiles along one axis (hundreds of row or column panels, ragged last panel) with the
+    shortest contraction the GEMM accepts: grid mapping, edge clamping and the k-major padding rows."""
+    X = synth.activations("laplace", M, K, seed=M % 97, device=DEV)
+    W = synth.weights(N, K, seed=N % 89, device=DEV)
+    Y = rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP)
+    Yd = rtl.dense_linear(X, W)
+    torch.cuda.synchronize()
+    rows = sampled_rows(M, min(M, 24), seed=3)
+    sel = torch.from_numpy(rows).to(DEV)
+    ref = oracle.sparse_linear_oracle(synth.bits(X[sel]), synth.bits(W), scope=oracle.GROUP)["Y"]
+    check_y(Y[sel], ref)
+    refd = oracle.dense_linear_oracle(synth.bits(X[sel]), synth.bits(W))
+    check_y(Yd[sel], refd)
+    vals, meta, _ = rtl.sparsify_pack(X, comp=rtl.COMP_GROUP)
+    r = oracle.sparsify_pack_oracle(synth.bits(X), scope=oracle.GROUP)
+    assert np.array_equal(meta.cpu().numpy(), r["meta"]) and np.array_equal(synth.bits(vals), r["vals"])
