@@ -9,7 +9,9 @@
  * General conventions
  *  - Every tensor pointer is a DEVICE pointer owned by the caller. The library never allocates,
  *    frees or synchronises; all work is enqueued on `stream` (a hipStream_t passed as void*,
- *    NULL = the default stream) and the call returns immediately.
+ *    NULL = the default stream) and the call returns immediately. Calls consist of kernel
+ *    launches only (no memset or copy nodes), so they may be recorded into a HIP graph once each
+ *    entry point has been called once outside a capture (the first call sets kernel attributes).
  *  - bf16 tensors are row-major with the contraction dimension K contiguous; `ld*` are row
  *    strides in ELEMENTS. Inputs are never modified; outputs are fully overwritten.
  *  - All argument checks happen before any launch, so error paths touch no memory:

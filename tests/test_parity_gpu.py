@@ -484,3 +484,46 @@ def test_large_grids_small_contraction(M, N, K):
     vals, meta, _ = rtl.sparsify_pack(X, comp=rtl.COMP_GROUP)
     r = oracle.sparsify_pack_oracle(synth.bits(X), scope=oracle.GROUP)
     assert np.array_equal(meta.cpu().numpy(), r["meta"]) and np.array_equal(synth.bits(vals), r["vals"])
+
+
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """The library only enqueues kernels on the caller's stream (no allocation, synchronisation or
+    memset), so a call sequence can be captured once and replayed; every replay must equal the
+    eager result on the inputs present at replay time."""
+    X, W = synth.workload("tiny", seed=0, device=DEV, M=300)
+    M, K = X.shape
+    N = W.shape[0]
+    LA, LB = synth.lora(N, K, 64, seed=3, device=DEV)
+    Wq = rtl.quantize_fp8(W)
+    xs = fp8_scale(X)
+    Xs = X.clone()                                    # static input buffer of the graph
+    Y1 = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    Y2, Y3 = torch.empty_like(Y1), torch.empty_like(Y1)
+    ws1 = torch.empty(rtl.sparse_linear_workspace(M, N, K, rtl.COMP_TENSOR) + 256, dtype=torch.uint8, device=DEV)
+    ws2 = torch.empty(rtl.sparse_lora_linear_workspace(M, N, K, 64) + 256, dtype=torch.uint8, device=DEV)
+    ws3 = torch.empty(rtl.sparse_linear_fp8_workspace(M, N, K) + 256, dtype=torch.uint8, device=DEV)
+
+    def run():
+        rtl.sparse_linear(Xs, W, comp=rtl.COMP_TENSOR, out=Y1, ws=ws1)
+        rtl.sparse_lora_linear(Xs, W, LA, LB, out=Y2, ws=ws2)
+        rtl.sparse_linear_fp8(Xs, Wq, xs, out=Y3, ws=ws3)
+
+    run()                                             # first calls (kernel attributes) outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for seed in (5, 6, 7):
+        Xn = synth.activations("laplace", M, K, seed=seed, device=DEV)
+        Xs.copy_(Xn)
+        for y in (Y1, Y2, Y3):
+            y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [Y1.clone(), Y2.clone(), Y3.clone()]
+        run()                                         # eager on the same inputs
+        torch.cuda.synchronize()
+        for a, b in zip(got, (Y1, Y2, Y3)):
+            assert torch.equal(a, b)
+        ref = oracle.sparse_linear_oracle(synth.bits(Xn), synth.bits(W), scope=oracle.TENSOR)["Y"]
+        check_y(got[0], ref)
