@@ -9,6 +9,9 @@
 // both spend the same number of matrix cycles per stage). Stages travel HBM/L2 -> LDS with
 // direct-to-LDS loads (no register staging) through a ring of LDS buffers, and each wave keeps the
 // operand fragments of the next sub-step in flight while the matrix core works on the current one.
+// The sparse kernel reads its compressed operand in the k-major layout the pack sweep writes
+// (values and metadata of a 256-row tile contiguous per stage: whole 128-byte lines only); the
+// dense operands X and W are the caller's row-major tensors.
 //
 // The compressed activation is the FIRST matrix operand of SMFMAC (the one that carries 2-of-4
 // structure along K), so tokens map to the instruction's rows and the weight rows (K contiguous)
