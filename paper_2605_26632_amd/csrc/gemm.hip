@@ -103,12 +103,15 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0() {   // vmcnt <= N, all LDS re
 
 // Per-stage LDS footprint. Rows of the A tile hold 64 bytes in both kernels (32 kept bf16 of 64
 // dense k, or 32 dense k); rows of the B tile hold 128 bytes (sparse) or 64 bytes (dense).
-template <bool SPARSE, int BM, int BN, int STAGES, int WAVES_M = 1, int WAVES_N = 1, bool FP8 = false>
+// D64 (dense only): stages of 64 dense k, 128-byte rows on both sides, so that every L2 request
+// of the row-major operands is a whole line; a sub-step is then two matrix instructions deep.
+template <bool SPARSE, int BM, int BN, int STAGES, int WAVES_M = 1, int WAVES_N = 1, bool FP8 = false,
+          bool D64 = false>
 struct Smem {
-    static constexpr int kABytes = BM * 64;
+    static constexpr int kABytes = BM * (D64 ? 128 : 64);
     static constexpr int kMetaRec = FP8 ? 16 : 8;   // metadata bytes per row and stage
     static constexpr int kMetaBytes = SPARSE ? BM * kMetaRec : 0;
-    static constexpr int kBBytes = SPARSE ? BN * 128 : BN * 64;
+    static constexpr int kBBytes = (SPARSE || D64) ? BN * 128 : BN * 64;
     static constexpr int kStage = kABytes + kMetaBytes + kBBytes;
     static constexpr int kRing = STAGES * kStage;
     // epilogue staging: every wave owns (BM / WAVES_M) rows of (BN / WAVES_N) bf16 plus 16 bytes
@@ -156,18 +159,21 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
 
 // MODE 0: plain linear. MODE 1 (sparse only): LoRA tail, the accumulators also receive T L_A^T before
 // the epilogue. MODE 2: split contraction, grid.y K ranges, fp32 partial tiles instead of Y.
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false>
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
+          bool D64 = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
+    static_assert(!D64 || (!SPARSE && MODE == 0), "64-k stages: plain dense kernel only");
     static_assert(MODE == 0 || (MODE == 1 && SPARSE) || (MODE == 2 && !SPARSE), "mode/operand combination");
     static_assert(!FP8 || (SPARSE && MODE == 0), "FP8 operands: plain sparse kernel only");
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
-    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8>;
+    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
     constexpr int ESZ = FP8 ? 1 : 2;                  // bytes per operand element
-    constexpr int KSTAGE = SPARSE ? 128 / ESZ : 32;   // dense k per stage
-    constexpr int A_ELEMS = 64 / ESZ;                 // elements of an A row per stage: 64 bytes
+    constexpr int KSTAGE = SPARSE ? 128 / ESZ : (D64 ? 64 : 32);   // dense k per stage
+    constexpr int A_ELEMS = D64 ? 64 : 64 / ESZ;      // elements of an A row per stage: 64 bytes (D64: 128)
+    constexpr int NMMA = D64 ? 2 * TM * TN : TM * TN; // matrix instructions of a sub-step
     constexpr int MREC = L::kMetaRec;                 // metadata bytes per row and stage
     constexpr int IXW = FP8 ? 2 : 1;                  // metadata words a lane holds per stage and row block
     // one wave-wide direct-to-LDS load moves 64 chunks of 16 bytes = 1 KiB
@@ -227,7 +233,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     for (int s = 0; s < A_PER_W; ++s) {
         const int p = (wave * A_PER_W + s) * 64 + lane;
         int row, c;
-        unswz4(p, row, c);
+        if constexpr (D64) unswz8(p, row, c); else unswz4(p, row, c);
         const int64_t gr = min((int64_t)row, rows_a - 1);
         // (the k-major buffer is padded to whole tiles: rows past M hold unspecified bytes whose
         //  products only reach outputs that are never stored)
@@ -238,7 +244,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     for (int s = 0; s < B_PER_W; ++s) {
         const int p = wave * B_CH + min(s * 64 + lane, B_CH - 1);   // masked lanes of a half load: any valid chunk
         int row, c;
-        if constexpr (SPARSE) unswz8(p, row, c); else unswz4(p, row, c);
+        if constexpr (SPARSE || D64) unswz8(p, row, c); else unswz4(p, row, c);
         const int64_t gr = min((int64_t)row, rows_b - 1);
         ob[s] = (uint32_t)(gr * a.ldw * ESZ + c * 16);
     }
@@ -294,7 +300,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         gload_one(kt, stage, std::integral_constant<int, 15>{});
     };
     constexpr int LOADS_PER_STAGE = A_PER_W + B_PER_W + (SPARSE ? M_PER_W : 0);
-    static_assert(LOADS_PER_STAGE <= 16 && (LOADS_PER_STAGE + 1) / 2 <= TM * TN, "loads are paired with matrix instructions");
+    static_assert(LOADS_PER_STAGE <= 16 && (LOADS_PER_STAGE + 1) / 2 <= NMMA, "loads are paired with matrix instructions");
 
     // ---- accumulators -------------------------------------------------------------------------
     f32x16 acc[TM][TN];
@@ -311,8 +317,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
 
     // operand fragments of one sub-step
     struct Frags {
-        Frag8 a[TM];
-        Frag16 b[TN];   // dense kernel uses b[j].u[0] only
+        std::conditional_t<D64, Frag16, Frag8> a[TM];   // D64: two 16-k halves
+        Frag16 b[TN];   // dense kernel with 32-k stages uses b[j].u[0] only
     };
     // metadata words of the current / next stage (sparse only); FP8: word 2 i + sub of row block i
     int ix_cur[TM * IXW], ix_nxt[TM * IXW];
@@ -321,12 +327,21 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         const uint8_t* base = smem + stage * L::kStage;
         const uint8_t* bB = base + L::kABytes + L::kMetaBytes;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            f.a[i].u = *reinterpret_cast<const uint4*>(base + swz4(arow0 + i * 32, 2 * (SPARSE ? kb : sub) + (SPARSE ? sub : kb)));
+        for (int i = 0; i < TM; ++i) {
+            if constexpr (D64) {
+                f.a[i].u[0] = *reinterpret_cast<const uint4*>(base + swz8(arow0 + i * 32, 4 * sub + kb));
+                f.a[i].u[1] = *reinterpret_cast<const uint4*>(base + swz8(arow0 + i * 32, 4 * sub + 2 + kb));
+            } else {
+                f.a[i].u = *reinterpret_cast<const uint4*>(base + swz4(arow0 + i * 32, 2 * (SPARSE ? kb : sub) + (SPARSE ? sub : kb)));
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int row = brow0 + j * 32;
-            if constexpr (SPARSE) {
+            if constexpr (D64) {
+                f.b[j].u[0] = *reinterpret_cast<const uint4*>(bB + swz8(row, 4 * sub + kb));
+                f.b[j].u[1] = *reinterpret_cast<const uint4*>(bB + swz8(row, 4 * sub + 2 + kb));
+            } else if constexpr (SPARSE) {
                 f.b[j].u[0] = *reinterpret_cast<const uint4*>(bB + swz8(row, 2 * sub + kb));
                 f.b[j].u[1] = *reinterpret_cast<const uint4*>(bB + swz8(row, 4 + 2 * sub + kb));
             } else {
@@ -364,6 +379,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
             } else {
                 ix[n] = *reinterpret_cast<const int*>(base + L::kABytes + (arow0 + n * 32) * 8 + kb * 4);
             }
+        } else if constexpr (D64) {
+            // 16-k half h of every fragment, first halves first (the order the instructions use them)
+            constexpr int h = n / (TM + TN), m = n % (TM + TN);
+            if constexpr (h < 2 && m < TM)
+                f.a[m].u[h] = *reinterpret_cast<const uint4*>(base + swz8(arow0 + m * 32, 4 * SUB + 2 * h + kb));
+            else if constexpr (h < 2)
+                f.b[m - TM].u[h] = *reinterpret_cast<const uint4*>(bB + swz8(brow0 + (m - TM) * 32, 4 * SUB + 2 * h + kb));
         } else if constexpr (n < NI + TM) {
             constexpr int i = n - NI;
             f.a[i].u = *reinterpret_cast<const uint4*>(
@@ -378,17 +400,30 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     };
     auto mma_one = [&](const Frags& f, const int (&ix)[TM * IXW], auto sub_tag, auto n_tag) {
         constexpr int SUB = decltype(sub_tag)::value;
-        constexpr int n = decltype(n_tag)::value, i = n % TM, j = n / TM;
-        if constexpr (n < TM * TN) {
-            if constexpr (FP8)
-                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(f.a[i].q, f.b[j].q, acc[i][j],
-                                                                         ix[2 * i + SUB], 0, 0);
-            else if constexpr (SPARSE)
-                acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[i].v, f.b[j].v, acc[i][j],
-                                                                      ix[i], 0, SUB);
-            else
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i].v, bf16x8(f.b[j].v.lo),
-                                                                    acc[i][j], 0, 0, 0);
+        constexpr int n = decltype(n_tag)::value;
+        constexpr int blk = n % (TM * TN), half = n / (TM * TN);   // half: 16-k half of a D64 sub-step
+        constexpr int i = blk % TM, j = blk / TM;
+        if constexpr (D64) {
+            if constexpr (n < NMMA) {
+                if constexpr (half == 0)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf16x8(f.a[i].v.lo), bf16x8(f.b[j].v.lo),
+                                                                        acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf16x8(f.a[i].v.hi), bf16x8(f.b[j].v.hi),
+                                                                        acc[i][j], 0, 0, 0);
+            }
+        } else {
+            if constexpr (n < TM * TN) {
+                if constexpr (FP8)
+                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(f.a[i].q, f.b[j].q, acc[i][j],
+                                                                             ix[2 * i + SUB], 0, 0);
+                else if constexpr (SPARSE)
+                    acc[i][j] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[i].v, f.b[j].v, acc[i][j],
+                                                                          ix[i], 0, SUB);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i].v, bf16x8(f.b[j].v.lo),
+                                                                        acc[i][j], 0, 0, 0);
+            }
         }
     };
     // Matrix work of sub-step SUB on fragments f. After each matrix instruction the wave issues two
@@ -400,15 +435,15 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
                    int rstage, Frags& rf, int (&rix)[TM * IXW], auto lo_tag, auto hi_tag, int kt_load, int buf) {
         constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
         constexpr bool READ = decltype(read_tag)::value;
-        static_assert(TM * TN <= 16 && HI - LO <= TM * TN, "unrolled by hand up to 16 matrix instructions");
-        static_assert((SPARSE ? 2 * TM + 2 * TN : TM + TN) <= 2 * TM * TN + 2, "two reads per matrix instruction must cover a fragment set");
+        static_assert(NMMA <= 16 && HI - LO <= NMMA, "unrolled by hand up to 16 matrix instructions");
+        static_assert(((SPARSE || D64) ? 2 * TM + 2 * TN : TM + TN) <= 2 * NMMA + 2, "two reads per matrix instruction must cover a fragment set");
 #define RTL_MMA_STEP(N)                                                                       \
         mma_one(f, ix, sub_tag, std::integral_constant<int, N>{});                            \
-        if constexpr (N < TM * TN) {                                                          \
+        if constexpr (N < NMMA) {                                                             \
             if constexpr (READ) {                                                             \
                 read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N>{});     \
                 read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N + 1>{}); \
-                if constexpr (N == TM * TN - 1) {                                             \
+                if constexpr (N == NMMA - 1) {                                                \
                     read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N + 2>{}); \
                     read_one(rstage, rsub_tag, rf, rix, std::integral_constant<int, 2 * N + 3>{}); \
                 }                                                                             \
@@ -446,7 +481,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     //   kt+STAGES (into the buffer of stage kt, which nobody reads any more).
     // Every stage has about two stage times to arrive and the request stream never bursts.
     // PENDING: whole stages younger than kt+1 in flight at the wait (compile-time per phase).
-    constexpr int SPLIT = (LOADS_PER_STAGE + 1) / 2;   // requests issued in the second half
+    // requests issued in the second half. A ring of two has no buffer to spare for the early part:
+    // all requests of stage kt+2 go out after the barrier of stage kt, one stage time ahead.
+    constexpr int SPLIT = STAGES == 2 ? LOADS_PER_STAGE : (LOADS_PER_STAGE + 1) / 2;
     using c0 = std::integral_constant<int, 0>;
     using cS = std::integral_constant<int, SPLIT>;
     using cL = std::integral_constant<int, LOADS_PER_STAGE>;
@@ -689,10 +726,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     }
 }
 
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false>
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
+          bool D64 = false>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
-    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8>;
-    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8>;
+    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
+    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>;
     static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -751,8 +789,9 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
         if (lora) return launch_cfg<true, 256, 256, 2, 4, 3, 1>(a, stream);
         return launch_cfg<true, 256, 256, 2, 4, 3>(a, stream);
     }
-    if (prefer_192(a.M, a.N, 32, 28)) return launch_cfg<false, 256, 192, 4, 2, 3>(a, stream);
-    return launch_cfg<false, 256, 256, 2, 4, 3>(a, stream);
+    // dense: stages of 64 k (whole-line requests on the row-major operands), ring of two
+    if (prefer_192(a.M, a.N, 64, 56)) return launch_cfg<false, 256, 192, 4, 2, 2, 0, false, true>(a, stream);
+    return launch_cfg<false, 256, 256, 2, 4, 2, 0, false, true>(a, stream);
 }
 
 // ---- LoRA down-projection: a skinny product (N = 64) bound by reading X once. 128-row tiles times
