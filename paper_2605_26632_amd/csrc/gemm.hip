@@ -162,7 +162,7 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
 template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
           bool D64 = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
-    static_assert(!D64 || (!SPARSE && MODE == 0), "64-k stages: plain dense kernel only");
+    static_assert(!D64 || (!SPARSE && MODE != 1), "64-k stages: dense kernels only");
     static_assert(MODE == 0 || (MODE == 1 && SPARSE) || (MODE == 2 && !SPARSE), "mode/operand combination");
     static_assert(!FP8 || (SPARSE && MODE == 0), "FP8 operands: plain sparse kernel only");
     constexpr int NW = WAVES_M * WAVES_N;
@@ -798,7 +798,7 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
 // enough K ranges to occupy every CU; the ranges are summed in a fixed order by a second kernel.
 static int lora_ranges(int64_t M, int64_t K, int* per_out) {
     const int64_t tiles = (M + 127) / 128;
-    const int KT = (int)(K / 32);
+    const int KT = (int)(K / 64);
     // Enough ranges to occupy every CU, and at least 8: workgroups that walk different parts of K
     // touch different memory channels at any moment (rows are a large power-of-two-ish stride apart),
     // which matters once M alone would fill the chip (measured at M = 16896, K = 12288: 163 us with
@@ -820,7 +820,7 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, 
     g.A = X; g.W = LB; g.partials = partials;
     g.M = M; g.N = kLoraRank; g.K = K; g.lda = ldx; g.ldw = ldlb; g.ldy = kLoraRank;
     g.splits = lora_down_splits(M, K);
-    hipError_t e = launch_cfg<false, 128, 64, 4, 1, 4, 2>(g, stream);
+    hipError_t e = launch_cfg<false, 128, 64, 4, 1, 4, 2, false, true>(g, stream);
     if (e != hipSuccess) return e;
     const int64_t n = M * kLoraRank;
     hipLaunchKernelGGL(lora_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
