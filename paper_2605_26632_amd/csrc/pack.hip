@@ -4,8 +4,9 @@
 // kept values + 2-bit positions (App. A operand format). One sweep over X; HBM-bandwidth bound:
 // 2 bytes read + 1.125 bytes written per input element.
 //
-// Mapping: one wavefront per row; a lane takes 8 consecutive bf16 (one 16-byte load = two
-// groups) per step and the wave walks the row in steps of 512 elements, so every load, the
+// Mapping: one wavefront per row (two for long rows, each taking a run of whole steps); a lane
+// takes 8 consecutive bf16 (one 16-byte load = two groups) per step and the wave walks the row in
+// steps of 512 elements, so every load, the
 // 8-byte value stores and the 4-byte metadata stores (four lanes' bytes gathered with DPP
 // quad permutes) are contiguous across the wave in the canonical (row-major) output. The
 // k-major output the GEMM streams (64-byte value blocks and 8-byte metadata records per row and
@@ -153,10 +154,16 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     const uint16_t* __restrict__ X, int64_t M, int K, int64_t ldx, float eps,
     void* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ vals_km,
     uint8_t* __restrict__ meta_km, int64_t Mpad, float* __restrict__ scale,
-    float* __restrict__ rowsums, const float* __restrict__ x_scale) {
+    float* __restrict__ rowsums, const float* __restrict__ x_scale, int parts) {
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    // `parts` waves share a row (NONE / GROUP only: nothing is summed along the row), each taking a
+    // run of whole 512-element steps; short rows then still give every SIMD enough waves in flight.
+    const int64_t gw = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t row = gw / parts;
     if (row >= M) return;  // whole wave leaves together
+    const int span = ((K + parts - 1) / parts + 511) / 512 * 512;
+    const int kbeg = (int)(gw % parts) * span;
+    const int kend = min(K, kbeg + span);
     const uint16_t* xr = X + row * ldx;
     // canonical value row (only dereferenced when vals != null): bf16 form / FP8 form
     uint16_t* vr = static_cast<uint16_t*>(vals) + row * (int64_t)(K / 2);
@@ -170,13 +177,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     float num = 0.f, den = 0.f;
     // rows of metadata are K/8 bytes: whole 32-bit words only when K is a multiple of 32
     const bool word_meta = (K & 31) == 0;
-    for (int k0 = 0; k0 < K; k0 += 512 * kUnroll) {
+    for (int k0 = kbeg; k0 < kend; k0 += 512 * kUnroll) {
         uint4 v[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int k = k0 + u * 512 + lane * 8;
             v[u] = make_uint4(0, 0, 0, 0);
-            if (k < K) v[u] = *reinterpret_cast<const uint4*>(xr + k);
+            if (k < kend) v[u] = *reinterpret_cast<const uint4*>(xr + k);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -191,7 +198,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
             // gather the metadata bytes of the four lanes of a quad into its first lane
             const uint32_t w = b | (quad_bcast<0x55>(b) << 8) | (quad_bcast<0xAA>(b) << 16) |
                                (quad_bcast<0xFF>(b) << 24);
-            if (k < K) {
+            if (k < kend) {
                 if constexpr (FP8) {
                     const uint32_t codes = g0.packed | (g1.packed << 16);
                     if (vals) *reinterpret_cast<uint32_t*>(vr8 + k / 2) = codes;
@@ -323,24 +330,29 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
                                   float* scale, float* rowsums, const float* x_scale, float* fused_scale,
                                   hipStream_t stream) {
     const int64_t Mpad = kmajor_rows(M);
-    const dim3 grid((unsigned)((M + kWavesPerBlock - 1) / kWavesPerBlock));
+    // Waves per row: two once each still has a full unrolled trip of work (measured: 34 -> 31 us at
+    // [4096,12288], 141 -> 131 us at [16896,12288], no change at K = 3072; four or more waves per row
+    // lose on the short rows). ROW / TENSOR sum along the row inside one wave.
+    int parts = 1;
+    if ((comp == RTL_COMP_NONE || comp == RTL_COMP_GROUP) && K >= 2 * 512 * kUnroll) parts = 2;
+    const dim3 grid((unsigned)((M * parts + kWavesPerBlock - 1) / kWavesPerBlock));
     const dim3 block(kWavesPerBlock * 64);
     switch (comp) {
         case RTL_COMP_NONE:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_NONE, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             break;
         case RTL_COMP_GROUP:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_GROUP, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             break;
         case RTL_COMP_ROW:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_ROW, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             break;
         case RTL_COMP_TENSOR:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_TENSOR, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps,
                                scale, x_scale, fused_scale);
             break;
