@@ -11,7 +11,10 @@ from .build import build as _build
 NONE, GROUP, ROW, TENSOR = 0, 1, 2, 3
 SCOPES = {"none": NONE, "group": GROUP, "row": ROW, "tensor": TENSOR}
 
-_lib = C.CDLL(_build())
+# RTL_ORACLE_LIB: load another build of the oracle instead (used only by the mutation test, which
+# plants mistakes in a copy of rtlynx_oracle.c and checks that the pins notice them).
+import os as _os
+_lib = C.CDLL(_os.environ.get("RTL_ORACLE_LIB") or _build())
 _i64 = C.c_int64
 _p = C.c_void_p
 
