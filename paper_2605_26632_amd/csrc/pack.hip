@@ -49,6 +49,20 @@ __device__ __forceinline__ uint32_t e4m3_pair(float t0, float t1) {
     return p;
 }
 
+// The compensation factor exactly as defined: every square rounded on its own, the sums in the
+// stated order, IEEE divide and square root. Squares of bf16 values are exact in fp32 unless they
+// fall below 2^-126, so the fused multiply-adds of the fast path give the same sums for ordinary
+// magnitudes; for tiny ones (|x| < 2^-63) only this unfused form matches a plain evaluation.
+__device__ __forceinline__ float exact_group_scale(float f0, float f1, float f2, float f3, float ka,
+                                                   float kb, float eps) {
+#pragma clang fp contract(off)
+    const float q0 = f0 * f0, q1 = f1 * f1, q2 = f2 * f2, q3 = f3 * f3;
+    const float num = ((q0 + q1) + q2) + q3;
+    const float qa = ka * ka, qb = kb * kb;
+    const float den = (qa + qb) + eps;
+    return sqrtf(num / den);
+}
+
 // d0 = x0 | x1 << 16, d1 = x2 | x3 << 16 (bf16 bit patterns). With FP8 the kept pair leaves as two
 // E4M3 codes of (s * x) * inv (inv = 1 / x_scale) in the low 16 bits of `packed`.
 template <int COMP, bool FP8 = false>
@@ -109,7 +123,7 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
                 const bool near8 = (w0 - 0x80000u < 32u) | (w1 - 0x80000u < 32u);
                 const bool tiny = (((b0 & 0x7FFFFFFFu) - 1u) < 0x3C7FFFFFu) | (((b1 & 0x7FFFFFFFu) - 1u) < 0x3C7FFFFFu);
                 if (near8 | tiny | odd_range) {
-                    s = sqrtf(o.num / d);
+                    s = exact_group_scale(f0, f1, f2, f3, ka, kb, eps);
                     t0 = (s * ka) * inv;
                     t1 = (s * kb) * inv;
                 }
@@ -117,7 +131,7 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
                 return o;
             }
             if (near | odd_range) {
-                s = sqrtf(o.num / d);
+                s = exact_group_scale(f0, f1, f2, f3, ka, kb, eps);
                 p0 = s * ka;
                 p1 = s * kb;
             }

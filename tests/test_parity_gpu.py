@@ -527,3 +527,20 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
             assert torch.equal(a, b)
         ref = oracle.sparse_linear_oracle(synth.bits(Xn), synth.bits(W), scope=oracle.TENSOR)["Y"]
         check_y(got[0], ref)
+
+
+@pytest.mark.parametrize("lo,hi", [(-30, -10), (-75, -62), (-80, -70), (-130, -60)])
+def test_pack_tiny_magnitudes_with_denormal_squares(lo, hi):
+    """|x| below 2^-63: the squares in the compensation factor are fp32 denormals, where a fused
+    multiply-add and a rounded product differ. Kept values must still match the oracle bit for bit,
+    with the paper's eps, with a tiny one and with none."""
+    rng = np.random.default_rng(1000 - lo * 7 - hi)
+    e = rng.integers(lo, hi, size=(64, 512))
+    x = (rng.choice([-1.0, 1.0], size=e.shape) * (1 + rng.integers(0, 128, size=e.shape) / 128.0)
+         * np.exp2(e.astype(np.float64))).astype(np.float32)
+    X = torch.from_numpy(x).to(torch.bfloat16).to(DEV)
+    for eps in (1e-8, 1e-30, 0.0):
+        check_pack(X, rtl.COMP_GROUP, eps=eps)
+    xs = fp8_scale(X)
+    for eps in (1e-8, 0.0):
+        check_pack_fp8(X, rtl.COMP_GROUP, xs, eps=eps)
