@@ -71,6 +71,8 @@ typedef enum {
  *   meta   [M, K/8] bytes, 4-byte aligned. Group g of a row sits in nibble (g & 1) of byte g/2;
  *          nibble = pos0 | pos1 << 2 with pos0 < pos1 the kept positions inside the group.
  *   scale  fp32 output, required for ROW ([M]) and TENSOR ([1]), ignored otherwise (may be NULL).
+ *          The two norms are accumulated in fp32: a row whose sum of squares exceeds the fp32
+ *          range (|x| around 1e17 and above) yields a NaN factor.
  *          s is constant along the contraction for these scopes, so it is handed out for an fp32
  *          multiplication of the GEMM result instead of being rounded into `vals`.
  *   workspace  device scratch of rtl_sparsify_pack_workspace(M, K, comp) bytes (0 unless TENSOR),

@@ -544,3 +544,24 @@ def test_pack_tiny_magnitudes_with_denormal_squares(lo, hi):
     xs = fp8_scale(X)
     for eps in (1e-8, 0.0):
         check_pack_fp8(X, rtl.COMP_GROUP, xs, eps=eps)
+
+
+def test_row_and_tensor_scopes_outside_their_fp32_domain():
+    """Documented limit: ROW / TENSOR norms are fp32 sums on the GPU. Rows of astronomically large
+    values overflow them (factor NaN) while the oracle's fp64 sums stay finite; selection, metadata
+    and kept values do not depend on the factor and stay bit-exact. GROUP works on every finite input."""
+    rng = np.random.default_rng(4)
+    huge = rng.choice([-1.0, 1.0], size=(8, 512)) * np.exp2(rng.integers(60, 100, size=(8, 512)).astype(np.float64))
+    X = torch.from_numpy(huge.astype(np.float32)).to(torch.bfloat16).to(DEV)
+    check_pack(X, rtl.COMP_GROUP)
+    for comp in (rtl.COMP_ROW, rtl.COMP_TENSOR):
+        vals, meta, scale = rtl.sparsify_pack(X, comp=comp)
+        torch.cuda.synchronize()
+        ref = oracle.sparsify_pack_oracle(synth.bits(X), scope=comp)
+        assert np.array_equal(meta.cpu().numpy(), ref["meta"]) and np.array_equal(synth.bits(vals), ref["vals"])
+        assert np.isfinite(ref["s"]).all() and not np.isfinite(scale.cpu().numpy()).any()
+    # just inside the domain both agree
+    ok = rng.choice([-1.0, 1.0], size=(8, 512)) * np.exp2(rng.integers(20, 55, size=(8, 512)).astype(np.float64))
+    Xo = torch.from_numpy(ok.astype(np.float32)).to(torch.bfloat16).to(DEV)
+    for comp in (rtl.COMP_ROW, rtl.COMP_TENSOR):
+        check_pack(Xo, comp)
