@@ -565,3 +565,23 @@ def test_row_and_tensor_scopes_outside_their_fp32_domain():
     Xo = torch.from_numpy(ok.astype(np.float32)).to(torch.bfloat16).to(DEV)
     for comp in (rtl.COMP_ROW, rtl.COMP_TENSOR):
         check_pack(Xo, comp)
+
+
+def test_sparse_linear_non_finite_activations_propagate_like_the_definition():
+    """A NaN or an infinity that survives the selection (they rank above every finite value) must show
+    up in exactly the outputs the masked dense definition gives; rows without them stay in tolerance."""
+    X, W = synth.workload("tiny", seed=2, device=DEV, M=96)
+    Xf = X.float().cpu().numpy().copy()
+    Xf[3, 17] = np.nan
+    Xf[10, 40] = np.inf
+    Xf[11, 41] = -np.inf
+    Xf[12, 100] = np.inf
+    Xf[12, 300] = -np.inf                      # +inf and -inf in one row: NaN wherever both weights are non-zero
+    Xn = torch.from_numpy(Xf).to(torch.bfloat16).to(DEV)
+    Y = y_to_np(rtl.sparse_linear(Xn, W, comp=rtl.COMP_NONE))
+    ref = oracle.sparse_linear_oracle(synth.bits(Xn), synth.bits(W), scope=oracle.NONE)["Y"]
+    assert np.array_equal(np.isnan(Y), np.isnan(ref))
+    assert np.array_equal(np.isposinf(Y), np.isposinf(ref)) and np.array_equal(np.isneginf(Y), np.isneginf(ref))
+    clean = np.isfinite(ref).all(axis=1)
+    assert clean.sum() == 96 - 4
+    check_y(torch.from_numpy(Y[clean]), ref[clean])
