@@ -68,6 +68,8 @@ def test_linear_entry_points_reject_bad_arguments():
         assert f(X=None) == 1 and f(W=None) == 1 and f(Y=None) == 1
         assert f(W=FAKE + 8) == 3 and f(ldx=68) == 3 and f(Y=FAKE + 1) == 3
         assert f(M=0) == 0 and f(N=0) == 0
+    for f in (dense, sparse):        # more output tiles than a 32-bit grid index can number
+        assert f(M=1 << 30, N=1 << 30, ldy=1 << 30) == 2
     for f in (dense, sparse):        # strides beyond the 32-bit tile-offset range are refused
         assert f(ldx=(1 << 22) + 8) == 2 and f(ldw=(1 << 22) + 8) == 2
     assert sparse(comp=9) == 5 and sparse(eps=float("inf")) == 5
