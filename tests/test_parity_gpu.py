@@ -585,3 +585,25 @@ def test_sparse_linear_non_finite_activations_propagate_like_the_definition():
     clean = np.isfinite(ref).all(axis=1)
     assert clean.sum() == 96 - 4
     check_y(torch.from_numpy(Y[clean]), ref[clean])
+
+
+def test_calls_on_two_streams_with_separate_workspaces():
+    """The library keeps no state between calls: two streams can run different problems at the same
+    time as long as each brings its own workspace and output. Results equal the default-stream ones."""
+    Xa, Wa = synth.workload("tiny", seed=1, device=DEV, M=700)
+    Xb, Wb = synth.workload("tiny", seed=2, device=DEV, M=333)
+    ya = rtl.sparse_linear(Xa, Wa)
+    yb = rtl.sparse_linear(Xb, Wb, comp=rtl.COMP_ROW)
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(5):
+        with torch.cuda.stream(sa):
+            za = rtl.sparse_linear(Xa, Wa)
+        with torch.cuda.stream(sb):
+            zb = rtl.sparse_linear(Xb, Wb, comp=rtl.COMP_ROW)
+        outs.append((za, zb))
+    sa.synchronize()
+    sb.synchronize()
+    for za, zb in outs:
+        assert torch.equal(za, ya) and torch.equal(zb, yb)
