@@ -303,6 +303,9 @@ def main():
         "dense_linear_tflops": round(flops / (dense_ms * 1e-3) / 1e12, 1),
         "hipblaslt_dense_tflops": round(flops / (blas_ms * 1e-3) / 1e12, 1),
         "sparse_cost_frac": round(pack_ms / (pack_ms + gemm_ms), 4),
+        # GEMM alone on the packed operand against the dense GEMMs (the paper's "kernel" speedup)
+        "gemm_speedup_vs_dense_linear": round(dense_ms / gemm_ms, 3),
+        "gemm_speedup_vs_hipblaslt_dense": round(blas_ms / gemm_ms, 3),
         "with_lora_r64": {"ms_per_step": round(lora_ms, 4), "tflops": round(flops / (lora_ms * 1e-3) / 1e12, 1),
                           "overhead_vs_sparse_linear": round(lora_ms / ms_per_step - 1.0, 4),
                           "speedup_vs_dense_linear": round(dense_ms / lora_ms, 3)},
