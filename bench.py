@@ -88,9 +88,17 @@ def run_sweep(args, torch, rtl, synth, dev, comp):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    skip = {k for k in args.dense_layers.split(",") if k}
+    unknown = skip - set(synth.SWEEP_LAYERS)
+    if unknown:
+        raise SystemExit("bench.py: unknown layer kinds in --dense-layers: %s" % sorted(unknown))
+
     def sparse_pass():
         for kind, x, w in layers:
-            rtl.sparse_linear(x, w, comp=comp, out=outs[kind], ws=ws)
+            if kind in skip:
+                rtl.dense_linear(x, w, out=outs[kind], ws=ws)
+            else:
+                rtl.sparse_linear(x, w, comp=comp, out=outs[kind], ws=ws)
 
     def dense_pass():
         for kind, x, w in layers:
@@ -105,8 +113,11 @@ def run_sweep(args, torch, rtl, synth, dev, comp):
     xs = [(x.float().abs().max() * (2.0 ** 0.5) / 448.0).reshape(1).to(torch.float32) for _, x, _ in layers]
 
     def fp8_pass():
-        for (kind, x, _), q, sc in zip(layers, wq, xs):
-            rtl.sparse_linear_fp8(x, q, sc, comp=comp, out=outs[kind], ws=ws)
+        for (kind, x, w), q, sc in zip(layers, wq, xs):
+            if kind in skip:
+                rtl.dense_linear(x, w, out=outs[kind], ws=ws)
+            else:
+                rtl.sparse_linear_fp8(x, q, sc, comp=comp, out=outs[kind], ws=ws)
 
     steps, warmup = min(args.steps, 10), min(args.warmup, 2)
     ms_sparse = timed(sparse_pass, steps, warmup)
@@ -118,8 +129,9 @@ def run_sweep(args, torch, rtl, synth, dev, comp):
         "value": round(flops / (ms_sparse * 1e-3) / 1e12, 1), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_sparse, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "sweep: %d blocks x (qkv, out_proj, fc1, fc2) at M=4608, comp=%s"
-                               % (args.sweep_blocks, args.comp), "linears": len(layers)},
+        "config": {"workload": "sweep: %d blocks x (qkv, out_proj, fc1, fc2) at M=4608, comp=%s%s"
+                               % (args.sweep_blocks, args.comp,
+                                  ", dense: " + "+".join(sorted(skip)) if skip else ""), "linears": len(layers)},
         "dense_linear_ms": round(ms_dense, 3), "hipblaslt_dense_ms": round(ms_blas, 3),
         "speedup_vs_dense_linear": round(ms_dense / ms_sparse, 3),
         "speedup_vs_hipblaslt_dense": round(ms_blas / ms_sparse, 3),
@@ -138,6 +150,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--sweep-blocks", type=int, default=60,
                     help="with --workload sweep: number of MMDiT blocks (4 linears each)")
+    ap.add_argument("--dense-layers", default="",
+                    help="with --workload sweep: comma-separated layer kinds (qkv,out_proj,fc1,fc2) that stay "
+                         "dense in the sparse pass, like the per-model skip lists of the paper's appendix")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (3 launches): reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
