@@ -16,7 +16,7 @@
 namespace rtl {
 namespace {
 
-constexpr int kWavesPerBlock = 4;
+constexpr int kWavesPerBlock = 8;
 constexpr int kUnroll = 3;   // 6 and 24 steps per row at K = 3072 / 12288 divide evenly
 
 __device__ __forceinline__ float bits_to_f32(uint32_t u) { return __uint_as_float(u); }
