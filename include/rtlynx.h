@@ -10,8 +10,9 @@
  *  - Every tensor pointer is a DEVICE pointer owned by the caller. The library never allocates,
  *    frees or synchronises; all work is enqueued on `stream` (a hipStream_t passed as void*,
  *    NULL = the default stream) and the call returns immediately. Calls consist of kernel
- *    launches only (no memset or copy nodes), so they may be recorded into a HIP graph once each
- *    entry point has been called once outside a capture (the first call sets kernel attributes).
+ *    launches only (no memset or copy nodes), so they may be recorded into a HIP graph; call
+ *    rtl_init() on the device once before the capture starts (the one-time set-up of a device,
+ *    which otherwise happens inside the first call, is not a stream operation).
  *  - bf16 tensors are row-major with the contraction dimension K contiguous; `ld*` are row
  *    strides in ELEMENTS. Inputs are never modified; outputs are fully overwritten.
  *  - All argument checks happen before any launch, so error paths touch no memory:
@@ -21,7 +22,10 @@
  *      RTL_ERR_ALIGN      a pointer or a row stride breaks the stated alignment
  *      RTL_ERR_WORKSPACE  workspace NULL or smaller than the matching *_workspace() query
  *      RTL_ERR_ARG        an enum value out of range, or eps negative / not finite
- *      RTL_ERR_HIP        the HIP runtime refused a launch (message via hipGetLastError)
+ *      RTL_ERR_HIP        the HIP runtime reports no usable device, or refused the set-up or a
+ *                         launch (message via hipGetLastError)
+ *      RTL_ERR_ARCH       the current device is not a gfx950 GPU (checked once per device, after
+ *                         the argument checks and before anything is launched)
  *  - M == 0 or N == 0 is RTL_OK with no launch.
  *  - Arithmetic: bf16 operands, fp32 accumulation, fp32 -> bf16 round-to-nearest-even on store.
  */
@@ -42,8 +46,15 @@ typedef enum {
     RTL_ERR_ALIGN = 3,
     RTL_ERR_WORKSPACE = 4,
     RTL_ERR_ARG = 5,
-    RTL_ERR_HIP = 6
+    RTL_ERR_HIP = 6,
+    RTL_ERR_ARCH = 7
 } rtl_status;
+
+/* One-time set-up of the CURRENT device: checks that it is a gfx950 GPU (else RTL_ERR_ARCH) and
+ * readies every kernel of the library for launch. Idempotent and thread-safe; every other entry
+ * point performs the same set-up by itself on its first call on a device, so calling rtl_init is
+ * only required before HIP-graph capture. Not a stream operation. */
+rtl_status rtl_init(void);
 
 /* Scope of the two norms in the compensation factor s (method section, "Norm-Compensated
  * Sparsification", and Alg. 1 step 4). The method section states it for one 1x4 group (GROUP,
@@ -68,7 +79,8 @@ typedef enum {
  *          comp == GROUP: the stored values are bf16_rne(s_g * x) with
  *              s_g = sqrtf((((x0^2+x1^2)+x2^2)+x3^2) / ((ka^2+kb^2)+eps))   (fp32, this order);
  *          otherwise the stored values are the untouched inputs.
- *   meta   [M, K/8] bytes, 4-byte aligned. Group g of a row sits in nibble (g & 1) of byte g/2;
+ *   meta   [M, K/8] bytes, 4-byte aligned (8-byte aligned if it is to be handed to
+ *          rtl_packed_linear). Group g of a row sits in nibble (g & 1) of byte g/2;
  *          nibble = pos0 | pos1 << 2 with pos0 < pos1 the kept positions inside the group.
  *   scale  fp32 output, required for ROW ([M]) and TENSOR ([1]), ignored otherwise (may be NULL).
  *          The two norms are accumulated in fp32: a row whose sum of squares exceeds the fp32
@@ -89,14 +101,17 @@ rtl_status rtl_sparsify_pack(const void* X, int64_t M, int64_t K, int64_t ldx,
  * (App. A: the 2-bit positions pick the matching rows of the dense operand), executed on the
  * structured-sparse matrix instructions; optional "+ b" of Alg. 2.
  *
- *   vals, meta  as written by rtl_sparsify_pack for an [M, K] activation. K % 64 == 0.
+ *   vals, meta  as written by rtl_sparsify_pack for an [M, K] activation (dense rows of K/2 values
+ *          and K/8 bytes). K % 64 == 0; vals 16-byte aligned, meta 8-byte aligned.
  *   row_scale   NULL, or fp32 [M]: Y[m, :] is multiplied by row_scale[m] in fp32 before the bias.
  *   tensor_scale NULL, or fp32 [1]: Y is multiplied by tensor_scale[0] likewise.
  *   W      [N, K] bf16, row stride ldw (>= K), 16-byte aligned base, ldw % 8 == 0.
  *   bias   NULL or bf16 [N].
  *   Y      [M, N] bf16, row stride ldy (>= N). 2-byte aligned is enough.
- *   workspace  rtl_packed_linear_workspace(M, N, K) bytes, 256-byte aligned (partial tiles of the
- *          split contraction; may be 0).
+ *   workspace  rtl_packed_linear_workspace(M, N, K) bytes (never 0 for a non-empty problem),
+ *          256-byte aligned: receives the k-major copy of the compressed operand that the tile
+ *          loop streams (a small re-layout kernel runs first; rtl_sparse_linear has its pack
+ *          sweep write that layout directly and skips this step).
  * ------------------------------------------------------------------------------------------- */
 size_t rtl_packed_linear_workspace(int64_t M, int64_t N, int64_t K);
 rtl_status rtl_packed_linear(const void* vals, const void* meta,
@@ -195,6 +210,24 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
                                  int64_t ldx, int64_t ldw, int64_t ldy,
                                  rtl_comp comp, float eps,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * rtl_diag_matrix_rate - diagnostic, not a step of the method: measures the issue rate of the matrix
+ * instruction the linears are built on with nothing else running (operands in registers), so that a
+ * benchmark can quote the tile loops against a ceiling measured on the device at hand.
+ *   kind      0: dense 32x32x16 bf16 instruction (Eq. linear_layer path), 1: structured-sparse
+ *             32x32x32 bf16 instruction (Alg. 1 "Y_s <- S(X) W^T" path).
+ *   operands  device, 3072 bytes, 16-byte aligned: bf16 bit patterns fed to every wave (all equal
+ *             values give the full-clock rate, random values the rate under real switching activity).
+ *   iters     1 .. 2^24; every wave issues 4 * iters instructions. blocks: 1 .. 65536 workgroups of
+ *             four waves (1024 = one wave per SIMD four times over on 256 compute units).
+ *   clocks    device uint64[2], written by the first wave: [0] shader-clock cycles, [1] ticks of the
+ *             constant 100 MHz counter between its first and last instruction.
+ *   sink      device float[1]; practically never written (keeps the arithmetic alive).
+ * Work per launch: blocks * 4 * 4 * iters instructions of 2*32*32*16 executed flops each.
+ * ------------------------------------------------------------------------------------------- */
+rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
+                                uint64_t* clocks, float* sink, void* stream);
 
 /* Human-readable name of a status code; never NULL. */
 const char* rtl_status_str(rtl_status s);

@@ -21,7 +21,7 @@ SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linea
            "rtl_dense_linear_workspace", "rtl_dense_linear",
            "rtl_quantize_fp8", "rtl_sparsify_pack_fp8_workspace", "rtl_sparsify_pack_fp8",
            "rtl_sparse_linear_fp8_workspace", "rtl_sparse_linear_fp8",
-           "rtl_status_str", "rtl_version"]
+           "rtl_diag_matrix_rate", "rtl_init", "rtl_status_str", "rtl_version"]
 
 _lib = None
 
@@ -72,6 +72,10 @@ def lib():
         L.rtl_sparse_linear_fp8_workspace.restype = sz
         L.rtl_sparse_linear_fp8.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, fl, vp, sz, vp]
         L.rtl_sparse_linear_fp8.restype = ci
+        L.rtl_diag_matrix_rate.argtypes = [ci, vp, i64, ci, vp, vp, vp]
+        L.rtl_diag_matrix_rate.restype = ci
+        L.rtl_init.argtypes = []
+        L.rtl_init.restype = ci
         L.rtl_status_str.argtypes = [ci]
         L.rtl_status_str.restype = C.c_char_p
         L.rtl_version.restype = C.c_char_p
@@ -85,6 +89,11 @@ def status_str(status):
 
 def version():
     return lib().rtl_version().decode()
+
+
+def init():
+    """rtl_init: one-time set-up of the current device (required only before HIP-graph capture)."""
+    _check(lib().rtl_init(), "rtl_init")
 
 
 def _p(t):
@@ -260,3 +269,17 @@ def sparse_linear_fp8(X, Wq, x_scale, bias=None, comp=COMP_GROUP, eps=1e-8, out=
                                  Wq.stride(0), Y.stride(0), comp, eps, _p(ws), ws.numel(), _stream())
     _check(st, "rtl_sparse_linear_fp8")
     return Y
+
+
+# ---- diagnostics ------------------------------------------------------------------------------
+
+def diag_matrix_rate(kind, operands, iters, blocks=1024):
+    """rtl_diag_matrix_rate: enqueue the issue-rate probe; returns (clocks uint64[2] as an int64 tensor,
+    executed flops of the launch). Timing is the caller's (events around the call)."""
+    _need_cuda(operands)
+    assert operands.numel() * operands.element_size() >= 3072
+    clocks = torch.zeros(2, dtype=torch.int64, device=operands.device)
+    sink = torch.zeros(1, dtype=torch.float32, device=operands.device)
+    st = lib().rtl_diag_matrix_rate(int(kind), _p(operands), int(iters), int(blocks), _p(clocks), _p(sink), _stream())
+    _check(st, "rtl_diag_matrix_rate")
+    return clocks, float(blocks) * 4 * 4 * iters * 2 * 32 * 32 * 16

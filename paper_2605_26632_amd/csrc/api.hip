@@ -1,9 +1,48 @@
 // C ABI of librtlynx: argument validation and dispatch. Every check precedes any launch, so the
 // error paths can be exercised on a host without a GPU.
 #include <cmath>
+#include <cstring>
+#include <mutex>
 #include "rtl_internal.h"
 
 namespace {
+
+// Per-device set-up state. A device is prepared once: its architecture is checked (the kernels
+// exist for gfx950 only) and the kernels are readied for launch (rtl::prepare_*_kernels).
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+    int state;   // 0 = not looked at yet, 1 = ready, -1 = not a gfx950 device
+};
+DeviceState g_dev[kMaxDevices];
+std::mutex g_dev_mutex;
+
+// Status of the current device: RTL_OK once prepared, RTL_ERR_ARCH for another architecture,
+// RTL_ERR_HIP when the runtime has no usable device.
+rtl_status device_ready() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RTL_ERR_HIP;
+    DeviceState& d = g_dev[dev];
+    if (d.state == 0) {
+        std::lock_guard<std::mutex> lock(g_dev_mutex);
+        if (d.state == 0) {
+            hipDeviceProp_t prop;
+            if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return RTL_ERR_HIP;
+            if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+                d.state = -1;
+            } else {
+                if (rtl::prepare_pack_kernels() != hipSuccess || rtl::prepare_gemm_kernels() != hipSuccess)
+                    return RTL_ERR_HIP;
+                d.state = 1;
+            }
+        }
+    }
+    return d.state == 1 ? RTL_OK : RTL_ERR_ARCH;
+}
+#define RTL_REQUIRE_DEVICE()                          \
+    do {                                              \
+        const rtl_status ready_ = device_ready();     \
+        if (ready_ != RTL_OK) return ready_;          \
+    } while (0)
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -39,12 +78,15 @@ const char* rtl_status_str(rtl_status s) {
         case RTL_ERR_ALIGN: return "RTL_ERR_ALIGN: pointer or stride alignment";
         case RTL_ERR_WORKSPACE: return "RTL_ERR_WORKSPACE: workspace missing or too small";
         case RTL_ERR_ARG: return "RTL_ERR_ARG: enum out of range or bad eps";
-        case RTL_ERR_HIP: return "RTL_ERR_HIP: HIP runtime error at launch";
+        case RTL_ERR_HIP: return "RTL_ERR_HIP: HIP runtime error (no device, set-up or launch)";
+        case RTL_ERR_ARCH: return "RTL_ERR_ARCH: the current device is not a gfx950 (MI355X) GPU";
     }
     return "RTL_ERR_UNKNOWN";
 }
 
-const char* rtl_version(void) { return "rtlynx-gfx950 0.1"; }
+const char* rtl_version(void) { return "rtlynx-gfx950 0.2"; }
+
+rtl_status rtl_init(void) { return device_ready(); }
 
 size_t rtl_sparsify_pack_workspace(int64_t M, int64_t K, rtl_comp comp) {
     (void)K;
@@ -66,6 +108,7 @@ rtl_status rtl_sparsify_pack(const void* X, int64_t M, int64_t K, int64_t ldx, r
     const size_t need = rtl_sparsify_pack_workspace(M, K, comp);
     if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     hipError_t e = rtl::launch_sparsify_pack(
         static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, static_cast<uint16_t*>(vals),
         static_cast<uint8_t*>(meta), nullptr, nullptr, scale, static_cast<float*>(workspace),
@@ -109,6 +152,7 @@ rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* ro
     const size_t need = rtl_packed_linear_workspace(M, N, K);
     if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     rtl::GemmArgs g{};
     uint8_t* vkm = static_cast<uint8_t*>(workspace);
     uint8_t* km = vkm + round_up(rtl::kmajor_val_bytes(M, K, 2), 256);
@@ -145,6 +189,7 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
     const SparseWs ws = sparse_ws(M, N, K, comp);
     if (!workspace || workspace_bytes < ws.total) return RTL_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     uint8_t* base = static_cast<uint8_t*>(workspace);
     float* scale = reinterpret_cast<float*>(base + ws.scale);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -191,6 +236,7 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
     const size_t need = p_off + round_up(rtl::lora_down_partial_bytes(M, K), 256);
     if (!workspace || workspace_bytes < need) return RTL_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     uint8_t* base = static_cast<uint8_t*>(workspace);
     float* scale = reinterpret_cast<float*>(base + ws.scale);
     uint16_t* T = reinterpret_cast<uint16_t*>(base + t_off);
@@ -228,6 +274,7 @@ rtl_status rtl_quantize_fp8(const void* W, int64_t rows, int64_t cols, int64_t l
     if (rows == 0 || cols == 0) return RTL_OK;
     if (!W || !Wq) return RTL_ERR_NULL;
     if (ld % 8 != 0 || ldq % 8 != 0 || !aligned(W, 16) || !aligned(Wq, 8)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     hipError_t e = rtl::launch_quantize_fp8(static_cast<const uint16_t*>(W), rows, cols, ld,
                                             static_cast<uint8_t*>(Wq), ldq,
                                             static_cast<hipStream_t>(stream));
@@ -252,6 +299,7 @@ rtl_status rtl_sparsify_pack_fp8(const void* X, int64_t M, int64_t K, int64_t ld
     const size_t need = rtl_sparsify_pack_fp8_workspace(M, K, comp);
     if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     hipError_t e = rtl::launch_sparsify_pack_fp8(
         static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, x_scale, static_cast<uint8_t*>(vals),
         static_cast<uint8_t*>(meta), nullptr, nullptr, scale, static_cast<float*>(workspace), nullptr,
@@ -276,6 +324,7 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
     const SparseWs ws = sparse_ws(M, N, K, comp, 1);
     if (!workspace || workspace_bytes < ws.total) return RTL_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     uint8_t* base = static_cast<uint8_t*>(workspace);
     float* scale = reinterpret_cast<float*>(base + ws.scale);
     float* fused = scale + (comp == RTL_COMP_ROW ? M : 1);   // x_scale times the TENSOR factor
@@ -299,6 +348,19 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
 
+rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
+                                uint64_t* clocks, float* sink, void* stream) {
+    if (kind < 0 || kind > 1) return RTL_ERR_ARG;
+    if (iters <= 0 || iters > ((int64_t)1 << 24) || blocks <= 0 || blocks > 65536) return RTL_ERR_SHAPE;
+    if (!operands || !clocks || !sink) return RTL_ERR_NULL;
+    if (!aligned(operands, 16) || !aligned(clocks, 8) || !aligned(sink, 4)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
+    hipError_t e = rtl::launch_matrix_rate(kind, operands, iters, blocks,
+                                           reinterpret_cast<unsigned long long*>(clocks), sink,
+                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
 size_t rtl_dense_linear_workspace(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
     return rtl::gemm_workspace_bytes(false, M, N, K);
@@ -313,6 +375,7 @@ rtl_status rtl_dense_linear(const void* X, const void* W, const void* bias, void
     const size_t need = rtl_dense_linear_workspace(M, N, K);
     if (need && (!workspace || workspace_bytes < need)) return RTL_ERR_WORKSPACE;
     if (need && !aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
     rtl::GemmArgs g{};
     g.A = X;
     g.W = W;

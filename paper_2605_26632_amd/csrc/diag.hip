@@ -1,0 +1,91 @@
+// Diagnostics of librtlynx: an issue-rate probe of the matrix instructions the linears are built on.
+//
+// Not a step of the method: it measures what the chip sustains when nothing but the matrix
+// instruction runs (operands in registers, no LDS, no memory traffic), so that the achieved rate of
+// the tile-loop kernels can be quoted against a measured ceiling as well as the published one. With
+// constant operands the stream runs at the full shader clock; with random operands the chip lowers
+// its clock under the switching activity, which is the realistic ceiling for real data.
+#include "rtl_internal.h"
+
+namespace rtl {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+union U8 {
+    uint4 u;
+    bf16x8 v;
+};
+union U16 {
+    uint4 u[2];
+    bf16x16 v;
+};
+
+// kind 0: v_mfma_f32_32x32x16_bf16, kind 1: v_smfmac_f32_32x32x32_bf16. One wave per SIMD, four
+// independent accumulators per wave so that consecutive instructions never wait for each other.
+// operands: 64 lanes x 48 bytes per wave slot (reused by every wave), any bf16 bit patterns.
+template <int KIND>
+__global__ __launch_bounds__(256) void matrix_rate_kernel(const uint4* __restrict__ operands, int64_t iters,
+                                                          unsigned long long* __restrict__ clocks,
+                                                          float* __restrict__ sink) {
+    const int lane = threadIdx.x & 63;
+    U8 a;
+    U16 b;
+    a.u = operands[lane * 3];
+    b.u[0] = operands[lane * 3 + 1];
+    b.u[1] = operands[lane * 3 + 2];
+    // metadata word: nibbles from the set {4, 8, 9, C, D, E} (pos0 < pos1), varied per lane
+    const uint32_t nib[6] = {0x4u, 0x8u, 0x9u, 0xCu, 0xDu, 0xEu};
+    uint32_t idx = 0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) idx |= nib[(lane + 5 * g + (b.u[0].x >> (3 * g))) % 6] << (4 * g);
+    f32x16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
+    unsigned long long c0 = 0, w0 = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        c0 = clock64();
+        w0 = wall_clock64();
+    }
+    for (int64_t it = 0; it < iters; ++it) {
+        if constexpr (KIND == 1) {
+            acc[0] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a.v, b.v, acc[0], (int)idx, 0, 0);
+            acc[1] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a.v, b.v, acc[1], (int)idx, 0, 1);
+            acc[2] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a.v, b.v, acc[2], (int)idx, 0, 0);
+            acc[3] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a.v, b.v, acc[3], (int)idx, 0, 1);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bf16x8(b.v.lo), acc[q], 0, 0, 0);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        clocks[0] = clock64() - c0;          // shader-clock cycles of this wave
+        clocks[1] = wall_clock64() - w0;     // ticks of the constant 100 MHz counter
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[q][r];
+    if (s == 12345.678f) sink[0] = s;        // keeps the accumulators alive; practically never true
+}
+
+}  // namespace
+
+hipError_t launch_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
+                              unsigned long long* clocks, float* sink, hipStream_t stream) {
+    if (kind == 1)
+        hipLaunchKernelGGL(matrix_rate_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const uint4*>(operands), iters, clocks, sink);
+    else
+        hipLaunchKernelGGL(matrix_rate_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const uint4*>(operands), iters, clocks, sink);
+    return hipGetLastError();
+}
+
+}  // namespace rtl

@@ -74,11 +74,11 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 // before the barrier that publishes the stage, and reads of older stages never wait for them.
 __device__ __forceinline__ void lds_dma16(const void* gaddr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_base), "v"(gaddr) : "memory");
+                 :: "s"(lds_base), "v"(gaddr) : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma4(const void* gaddr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
-                 :: "s"(lds_base), "v"(gaddr) : "memory");
+                 :: "s"(lds_base), "v"(gaddr) : "memory", "m0");
 }
 // Same with a wave-uniform 64-bit base (SGPR pair) plus a 32-bit per-lane byte offset: the per-lane
 // state of a stream shrinks to one register and the walk along K is a scalar addition.
@@ -90,11 +90,11 @@ __device__ __forceinline__ uint64_t uniform64(const void* p) {   // pin a wave-u
 }
 __device__ __forceinline__ void lds_dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_base), "v"(voff), "s"(uniform64(sbase)) : "memory");
+                 :: "s"(lds_base), "v"(voff), "s"(uniform64(sbase)) : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma4_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :: "s"(lds_base), "v"(voff), "s"(uniform64(sbase)) : "memory");
+                 :: "s"(lds_base), "v"(voff), "s"(uniform64(sbase)) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_lgkm0() {   // vmcnt <= N, all LDS reads returned
@@ -726,18 +726,24 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     }
 }
 
+// The tile loops need more dynamic LDS than the default limit of a launch: the limit is raised once
+// per kernel by prepare_cfg (called for every configuration from prepare_gemm_kernels, i.e. from
+// rtl_init or from the first entry-point call on a device), never from a launch, so that launches
+// consist of the kernel node only and can be recorded into a HIP graph.
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
+          bool D64 = false>
+hipError_t prepare_cfg() {
+    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
+    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               L::kTotal);
+}
+
 template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
           bool D64 = false>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
     auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>;
-    static bool attr_set = false;   // per instantiation; idempotent, so a race is harmless
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, L::kTotal);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int64_t tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)tiles, MODE == 2 ? (unsigned)a.splits : 1u);
     hipLaunchKernelGGL(kern, grid, dim3(WAVES_M * WAVES_N * 64), L::kTotal, stream, a);
@@ -773,6 +779,22 @@ static bool prefer_192(int64_t M, int64_t N, int64_t kb256 = 51, int64_t kb192 =
     const int64_t t256 = tm * ((N + 255) / 256), t192 = tm * ((N + 191) / 192);
     const int64_t c256 = (t256 + kCUs - 1) / kCUs * kb256, c192 = (t192 + kCUs - 1) / kCUs * kb192;
     return c192 < c256;
+}
+
+// Every configuration launch_gemm and launch_lora_down can pick.
+hipError_t prepare_gemm_kernels() {
+    hipError_t e = hipSuccess;
+    auto run = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+    run(prepare_cfg<true, 256, 192, 4, 2, 3, 0, true>());
+    run(prepare_cfg<true, 256, 256, 2, 4, 3, 0, true>());
+    run(prepare_cfg<true, 256, 192, 4, 2, 3, 1>());
+    run(prepare_cfg<true, 256, 192, 4, 2, 3>());
+    run(prepare_cfg<true, 256, 256, 2, 4, 3, 1>());
+    run(prepare_cfg<true, 256, 256, 2, 4, 3>());
+    run(prepare_cfg<false, 256, 192, 4, 2, 2, 0, false, true>());
+    run(prepare_cfg<false, 256, 256, 2, 4, 2, 0, false, true>());
+    run(prepare_cfg<false, 128, 64, 4, 1, 4, 2, false, true>());
+    return e;
 }
 
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {

@@ -330,6 +330,12 @@ __global__ __launch_bounds__(256) void operand_to_kmajor_kernel(const uint16_t* 
 
 }  // namespace
 
+// Querying one kernel makes the runtime load this translation unit's code object.
+hipError_t prepare_pack_kernels() {
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(operand_to_kmajor_kernel));
+}
+
 hipError_t launch_operand_to_kmajor(const uint16_t* vals, const uint8_t* meta, int64_t M, int64_t K,
                                     uint8_t* vals_km, uint8_t* meta_km, hipStream_t stream) {
     const int64_t KB = K / 64, n = M * KB * 4;

@@ -71,6 +71,11 @@ struct GemmArgs {
     bool fp8;               // sparse only: E4M3 operands, K % 128 == 0, 16-byte metadata records
 };
 size_t gemm_workspace_bytes(bool sparse, int64_t M, int64_t N, int64_t K);
+// One-time set-up per device (rtl_init, or the first entry-point call): raises the dynamic-LDS limit
+// of every tile-loop kernel and makes the runtime load both code objects, so that later launches
+// are plain kernel nodes (HIP-graph capture needs no warm-up call).
+hipError_t prepare_gemm_kernels();
+hipError_t prepare_pack_kernels();
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream);
 
 // LoRA down-projection T = X L_B^T ([2][M,64] bf16 hi/lo planes): split-K partial products +
@@ -80,5 +85,13 @@ int lora_down_splits(int64_t M, int64_t K);
 size_t lora_down_partial_bytes(int64_t M, int64_t K);
 hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
                             int64_t K, float* partials, uint16_t* T, hipStream_t stream);
+
+// ---- diagnostics (diag.hip) -------------------------------------------------------------------
+// Issue-rate probe: `blocks` workgroups of four waves, each wave issuing 4 * iters matrix
+// instructions (kind 0: dense 32x32x16 bf16, kind 1: structured-sparse 32x32x32 bf16) on register
+// operands read once from `operands` (3072 bytes). clocks[0..1]: shader cycles and 100 MHz ticks
+// of the first wave.
+hipError_t launch_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
+                              unsigned long long* clocks, float* sink, hipStream_t stream);
 
 }  // namespace rtl

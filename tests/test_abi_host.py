@@ -22,8 +22,15 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    for s in range(7):
+    for s in range(8):
         assert rtl.status_str(s).startswith("RTL_")
+    assert rtl.status_str(7).startswith("RTL_ERR_ARCH") and rtl.status_str(99) == "RTL_ERR_UNKNOWN"
+
+
+def test_init_reports_a_status_without_a_gpu():
+    """rtl_init never aborts: without a usable device it reports RTL_ERR_HIP, on another AMD GPU
+    RTL_ERR_ARCH, on a gfx950 device RTL_OK."""
+    assert rtl.lib().rtl_init() in (0, 6, 7)
 
 
 FAKE = 0x10000  # non-null, 256-byte aligned, never dereferenced: validation precedes any launch
