@@ -137,6 +137,28 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * rtl_sparse_linear_static - rtl_sparse_linear for callers that cannot allocate device memory or
+ * pass a workspace: code running under HIP-graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc. Same arguments, checks, kernels and results as rtl_sparse_linear, but the
+ * scratch (compressed operand, factors) lives in a fixed device array inside the library of
+ * RTL_STATIC_SCRATCH_BYTES bytes, which every GPU the library is used on holds until the process
+ * ends. The call allocates and frees nothing.
+ *   - Problems whose rtl_sparse_linear_workspace(M, N, K, comp) exceeds RTL_STATIC_SCRATCH_BYTES
+ *     are refused with RTL_ERR_WORKSPACE (64 MiB covers every layer shape with M <= 4608 and
+ *     K <= 12288, e.g. the [4096, 12288] x [3072, 12288] MLP-down layer).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it; serialise them, or use rtl_sparse_linear with separate
+ *     workspaces. Nothing in the array needs to survive between calls.
+ *   - The first call on a device (or rtl_init) looks up the array's device address; do that
+ *     before a graph capture starts.
+ * ------------------------------------------------------------------------------------------- */
+#define RTL_STATIC_SCRATCH_BYTES (64u * 1024u * 1024u)
+rtl_status rtl_sparse_linear_static(const void* X, const void* W, const void* bias, void* Y,
+                                    int64_t M, int64_t N, int64_t K,
+                                    int64_t ldx, int64_t ldw, int64_t ldy,
+                                    rtl_comp comp, float eps, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * rtl_sparse_lora_linear - the whole of Alg. 1 including its LoRA residual (Eq. sparse+lora):
  *     Y = compensate(sparsify_2:4(X)) W^T + X (L_A L_B)^T (+ b).
  * The residual is evaluated as (X L_B^T) L_A^T: a skinny product T = X L_B^T ([M,R], kept in the

@@ -16,7 +16,7 @@ COMP_NONE, COMP_GROUP, COMP_ROW, COMP_TENSOR = 0, 1, 2, 3
 COMP = {"none": COMP_NONE, "group": COMP_GROUP, "row": COMP_ROW, "tensor": COMP_TENSOR}
 
 SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linear_workspace",
-           "rtl_packed_linear", "rtl_sparse_linear_workspace", "rtl_sparse_linear",
+           "rtl_packed_linear", "rtl_sparse_linear_workspace", "rtl_sparse_linear", "rtl_sparse_linear_static",
            "rtl_sparse_lora_linear_workspace", "rtl_sparse_lora_linear",
            "rtl_dense_linear_workspace", "rtl_dense_linear",
            "rtl_quantize_fp8", "rtl_sparsify_pack_fp8_workspace", "rtl_sparsify_pack_fp8",
@@ -53,6 +53,8 @@ def lib():
         L.rtl_sparse_linear_workspace.restype = sz
         L.rtl_sparse_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, fl, vp, sz, vp]
         L.rtl_sparse_linear.restype = ci
+        L.rtl_sparse_linear_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, fl, vp]
+        L.rtl_sparse_linear_static.restype = ci
         L.rtl_sparse_lora_linear_workspace.argtypes = [i64, i64, i64, i64, ci]
         L.rtl_sparse_lora_linear_workspace.restype = sz
         L.rtl_sparse_lora_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64,
@@ -175,6 +177,21 @@ def sparse_linear(X, W, bias=None, comp=COMP_GROUP, eps=1e-8, out=None, ws=None)
     st = L.rtl_sparse_linear(_p(X), _p(W), _p(bias), _p(Y), M, N, K, X.stride(0), W.stride(0),
                              Y.stride(0), comp, eps, _p(ws), ws.numel(), _stream())
     _check(st, "rtl_sparse_linear")
+    return Y
+
+
+STATIC_SCRATCH_BYTES = 64 * 1024 * 1024     # RTL_STATIC_SCRATCH_BYTES of the header
+
+
+def sparse_linear_static(X, W, Y, bias=None, comp=COMP_GROUP, eps=1e-8):
+    """rtl_sparse_linear_static: rtl_sparse_linear on the library's fixed scratch; the caller passes
+    inputs and the output, nothing is allocated (not by the library, not here)."""
+    _need_cuda(X, W, Y)
+    M, K = X.shape
+    N = W.shape[0]
+    st = lib().rtl_sparse_linear_static(_p(X), _p(W), _p(bias), _p(Y), M, N, K, X.stride(0), W.stride(0),
+                                        Y.stride(0), comp, eps, _stream())
+    _check(st, "rtl_sparse_linear_static")
     return Y
 
 

@@ -7,18 +7,26 @@
 
 namespace {
 
+// Scratch of rtl_sparse_linear_static, the entry point for callers that cannot allocate: a
+// fixed array in device memory that every GPU the library runs on holds until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the device address it
+// yields (one per device) is what kernels and launches receive.
+static __device__ __align__(256) unsigned char scratch[RTL_STATIC_SCRATCH_BYTES];
+
 // Per-device set-up state. A device is prepared once: its architecture is checked (the kernels
-// exist for gfx950 only) and the kernels are readied for launch (rtl::prepare_*_kernels).
+// exist for gfx950 only), the kernels are readied for launch (rtl::prepare_*_kernels) and the
+// address of this device's copy of `scratch` is looked up.
 constexpr int kMaxDevices = 64;
 struct DeviceState {
-    int state;   // 0 = not looked at yet, 1 = ready, -1 = not a gfx950 device
+    int state;            // 0 = not looked at yet, 1 = ready, -1 = not a gfx950 device
+    void* scratch_ptr;    // device address of `scratch` on this device (valid when state == 1)
 };
 DeviceState g_dev[kMaxDevices];
 std::mutex g_dev_mutex;
 
 // Status of the current device: RTL_OK once prepared, RTL_ERR_ARCH for another architecture,
 // RTL_ERR_HIP when the runtime has no usable device.
-rtl_status device_ready() {
+rtl_status device_ready(void** scratch_out = nullptr) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RTL_ERR_HIP;
     DeviceState& d = g_dev[dev];
@@ -32,10 +40,14 @@ rtl_status device_ready() {
             } else {
                 if (rtl::prepare_pack_kernels() != hipSuccess || rtl::prepare_gemm_kernels() != hipSuccess)
                     return RTL_ERR_HIP;
+                void* ptr = nullptr;
+                if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return RTL_ERR_HIP;
+                d.scratch_ptr = ptr;
                 d.state = 1;
             }
         }
     }
+    if (d.state == 1 && scratch_out) *scratch_out = d.scratch_ptr;
     return d.state == 1 ? RTL_OK : RTL_ERR_ARCH;
 }
 #define RTL_REQUIRE_DEVICE()                          \
@@ -178,21 +190,13 @@ size_t rtl_sparse_linear_workspace(int64_t M, int64_t N, int64_t K, rtl_comp com
     return sparse_ws(M, N, K, comp).total;
 }
 
-rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, void* Y, int64_t M,
-                             int64_t N, int64_t K, int64_t ldx, int64_t ldw, int64_t ldy,
-                             rtl_comp comp, float eps, void* workspace, size_t workspace_bytes,
-                             void* stream) {
-    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
-    rtl_status st = check_linear(X, W, Y, M, N, K, ldx, ldw, ldy, K);
-    if (st != RTL_OK || M == 0 || N == 0) return st;
-    if (bias && !aligned(bias, 2)) return RTL_ERR_ALIGN;
-    const SparseWs ws = sparse_ws(M, N, K, comp);
-    if (!workspace || workspace_bytes < ws.total) return RTL_ERR_WORKSPACE;
-    if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
-    RTL_REQUIRE_DEVICE();
-    uint8_t* base = static_cast<uint8_t*>(workspace);
+// Pack sweep + tile loop of rtl_sparse_linear on an already validated problem, with `base` the
+// 256-byte aligned scratch of sparse_ws(M, N, K, comp).total bytes (caller's workspace, or the
+// static array of rtl_sparse_linear_static).
+static rtl_status sparse_linear_on(uint8_t* base, const SparseWs& ws, const void* X, const void* W,
+                                   const void* bias, void* Y, int64_t M, int64_t N, int64_t K, int64_t ldx,
+                                   int64_t ldw, int64_t ldy, rtl_comp comp, float eps, hipStream_t s) {
     float* scale = reinterpret_cast<float*>(base + ws.scale);
-    hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = rtl::launch_sparsify_pack(
         static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr, base + ws.vals,
         base + ws.meta, scale, reinterpret_cast<float*>(base + ws.pack), s);
@@ -209,6 +213,38 @@ rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, voi
     g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, s);
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+rtl_status rtl_sparse_linear(const void* X, const void* W, const void* bias, void* Y, int64_t M,
+                             int64_t N, int64_t K, int64_t ldx, int64_t ldw, int64_t ldy,
+                             rtl_comp comp, float eps, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    rtl_status st = check_linear(X, W, Y, M, N, K, ldx, ldw, ldy, K);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (bias && !aligned(bias, 2)) return RTL_ERR_ALIGN;
+    const SparseWs ws = sparse_ws(M, N, K, comp);
+    if (!workspace || workspace_bytes < ws.total) return RTL_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
+    return sparse_linear_on(static_cast<uint8_t*>(workspace), ws, X, W, bias, Y, M, N, K, ldx, ldw, ldy, comp,
+                            eps, static_cast<hipStream_t>(stream));
+}
+
+rtl_status rtl_sparse_linear_static(const void* X, const void* W, const void* bias, void* Y, int64_t M,
+                                    int64_t N, int64_t K, int64_t ldx, int64_t ldw, int64_t ldy,
+                                    rtl_comp comp, float eps, void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    rtl_status st = check_linear(X, W, Y, M, N, K, ldx, ldw, ldy, K);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (bias && !aligned(bias, 2)) return RTL_ERR_ALIGN;
+    const SparseWs ws = sparse_ws(M, N, K, comp);
+    if (ws.total > (size_t)RTL_STATIC_SCRATCH_BYTES) return RTL_ERR_WORKSPACE;   // problem too large for the fixed scratch
+    void* base = nullptr;
+    const rtl_status ready = device_ready(&base);    // first call on a device: looks up this device's array
+    if (ready != RTL_OK) return ready;
+    return sparse_linear_on(static_cast<uint8_t*>(base), ws, X, W, bias, Y, M, N, K, ldx, ldw, ldy, comp, eps,
+                            static_cast<hipStream_t>(stream));
 }
 
 // rtl_sparse_lora_linear workspace: [rtl_sparse_linear workspace | T as two bf16 planes [2][M,64] | fp32 partials]
