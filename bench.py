@@ -61,57 +61,56 @@ def _read_number(path):
         return None
 
 
-def gpu_state_under_load(step, torch, seconds=0.25):
-    """Shader clock and board power WHILE `step` runs back to back: the amdgpu hwmon files are polled
-    from this thread between batches of launches (no synchronisation in between, so the queue stays
-    full). Falls back to one `rocm-smi` reading taken while the load runs. Values are null when
-    neither source is readable on the box."""
+def gpu_state_under_load(step, torch):
+    """Shader clock and board power WHILE `step` runs back to back. The clock comes from one `rocm-smi`
+    reading taken while this thread keeps the queue full; the power from the amdgpu hwmon file
+    (power1_input / power1_average, microwatts), polled between batches of launches during the same
+    period. Values are null when a source is not readable on the box."""
     import glob
     import subprocess
-    out = {"sclk_mhz": None, "power_w": None, "source": None, "samples": 0}
-    freq = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/freq1_input"))
-    if freq and _read_number(freq[0]) is not None:
-        hw = os.path.dirname(freq[0])
-        pw = next((q for q in (os.path.join(hw, "power1_average"), os.path.join(hw, "power1_input"))
-                   if _read_number(q) is not None), None)
-        f_s, p_s = [], []
-        t_end = time.perf_counter() + seconds
-        while time.perf_counter() < t_end:
-            for _ in range(8):
-                step()
-            f_s.append(_read_number(freq[0]))
-            if pw:
-                p_s.append(_read_number(pw))
-        torch.cuda.synchronize()
-        f_s = [v for v in f_s if v]
-        p_s = [v for v in p_s if v]
-        if f_s:
-            out.update(sclk_mhz={"mean": round(sum(f_s) / len(f_s) / 1e6, 0), "min": round(min(f_s) / 1e6, 0),
-                                 "max": round(max(f_s) / 1e6, 0)},
-                       source="amdgpu hwmon freq1_input / power1_*, polled while the step runs back to back",
-                       samples=len(f_s))
-        if p_s:
-            out["power_w"] = {"mean": round(sum(p_s) / len(p_s) / 1e6, 0), "max": round(max(p_s) / 1e6, 0)}
-        if f_s:
-            return out
+    out = {"sclk_mhz": None, "power_w": None, "power_cap_w": None, "source": None}
+    cap = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
+    if cap and _read_number(cap[0]) is not None:
+        out["power_cap_w"] = round(_read_number(cap[0]) / 1e6, 0)
+    pw = None
+    for name in ("power1_average", "power1_input"):
+        hits = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/" + name))
+        if hits and _read_number(hits[0]) is not None:
+            pw = hits[0]
+            break
+    p_s = []
     try:
-        proc = subprocess.Popen(["rocm-smi", "--showclocks", "--showpower", "--json"], stdout=subprocess.PIPE,
+        proc = subprocess.Popen(["rocm-smi", "--showclocks", "--json"], stdout=subprocess.PIPE,
                                 stderr=subprocess.DEVNULL, text=True)
-        t_end = time.perf_counter() + 20.0
-        while proc.poll() is None and time.perf_counter() < t_end:
-            for _ in range(8):
-                step()
-            torch.cuda.synchronize()
+    except Exception:
+        proc = None
+    t_end = time.perf_counter() + (20.0 if proc else 0.25)
+    while time.perf_counter() < t_end and (proc is None or proc.poll() is None):
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        if pw:
+            p_s.append(_read_number(pw))
+    torch.cuda.synchronize()
+    sources = []
+    if proc is not None:
         if proc.poll() is None:
             proc.kill()
-        txt = proc.communicate()[0]
-        card = next(iter(json.loads(txt).values()))
-        sclk = next((v for k, v in card.items() if k.lower().startswith("sclk clock speed")), None)
-        power = next((v for k, v in card.items() if "power" in k.lower() and "(w)" in k.lower()), None)
-        out.update(sclk_mhz=sclk, power_w=power, source="rocm-smi --showclocks --showpower, read while the step "
-                   "runs back to back", samples=1)
-    except Exception:
-        torch.cuda.synchronize()
+        try:
+            card = next(iter(json.loads(proc.communicate()[0]).values()))
+            sclk = next((v for k, v in card.items() if k.lower().startswith("sclk")), None)
+            if sclk is not None:
+                digits = "".join(ch for ch in str(sclk) if ch.isdigit() or ch == ".")
+                out["sclk_mhz"] = float(digits) if digits else None
+                sources.append("sclk: rocm-smi --showclocks, read while the step runs back to back")
+        except Exception:
+            pass
+    p_s = [v for v in p_s if v]
+    if p_s:
+        out["power_w"] = {"mean": round(sum(p_s) / len(p_s) / 1e6, 0), "max": round(max(p_s) / 1e6, 0),
+                          "samples": len(p_s)}
+        sources.append("power: amdgpu hwmon %s, polled during the same period" % os.path.basename(pw))
+    out["source"] = "; ".join(sources) or None
     return out
 
 
