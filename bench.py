@@ -241,6 +241,9 @@ def main():
     ap.add_argument("--dense-layers", default="",
                     help="with --workload sweep: comma-separated layer kinds (qkv,out_proj,fc1,fc2) that stay "
                          "dense in the sparse pass, like the per-model skip lists of the paper's appendix")
+    ap.add_argument("--only-core", action="store_true",
+                    help="time only the step, its pack kernel and the two dense GEMMs (no LoRA, FP8, cold-cache, "
+                         "peak-probe or clock legs): the short command the rocprofv3 summaries under profiles/ use")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (3 launches): reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -306,17 +309,19 @@ def main():
     t_dense = event_times(lambda: rtl.dense_linear(X, W, out=Y, ws=wsd), n_ev, 10, torch)
     t_blas = event_times(lambda: torch.matmul(X, W.t(), out=Y), n_ev, 10, torch)
     # whole Alg. 1 with its rank-64 LoRA residual (context: the paper's linear-layer figures include it)
-    LA, LB = synth.lora(N, K, 64, seed=3, device=dev)
-    wsl = torch.empty(rtl.sparse_lora_linear_workspace(M, N, K, 64, comp) + 256, dtype=torch.uint8, device=dev)
-    t_lora = event_times(lambda: rtl.sparse_lora_linear(X, W, LA, LB, comp=comp, out=Y, ws=wsl), n_ev, 10, torch)
+    t_lora = None
+    if not args.only_core:
+        LA, LB = synth.lora(N, K, 64, seed=3, device=dev)
+        wsl = torch.empty(rtl.sparse_lora_linear_workspace(M, N, K, 64, comp) + 256, dtype=torch.uint8, device=dev)
+        t_lora = event_times(lambda: rtl.sparse_lora_linear(X, W, LA, LB, comp=comp, out=Y, ws=wsl), n_ev, 10, torch)
     # FP8 composition (W8A8 + 2:4 activation sparsity; context, another precision than `value`)
-    xs8 = (X.float().abs().max() * (2.0 ** 0.5) / 448.0).reshape(1).to(torch.float32)
-    Wq = rtl.quantize_fp8(W)
-    ws8 = torch.empty(rtl.sparse_linear_fp8_workspace(M, N, K, comp) + 256, dtype=torch.uint8, device=dev)
-    v8 = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
-    m8 = torch.empty((M, K // 8), dtype=torch.uint8, device=dev)
     fp8 = None
-    if K % 128 == 0:
+    if K % 128 == 0 and not args.only_core:
+        xs8 = (X.float().abs().max() * (2.0 ** 0.5) / 448.0).reshape(1).to(torch.float32)
+        Wq = rtl.quantize_fp8(W)
+        ws8 = torch.empty(rtl.sparse_linear_fp8_workspace(M, N, K, comp) + 256, dtype=torch.uint8, device=dev)
+        v8 = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        m8 = torch.empty((M, K // 8), dtype=torch.uint8, device=dev)
         t_fp8 = event_times(lambda: rtl.sparse_linear_fp8(X, Wq, xs8, comp=comp, out=Y, ws=ws8), n_ev, 10, torch)
         t_pack8 = event_times(lambda: rtl.sparsify_pack_fp8(X, xs8, comp=comp, out=(v8, m8)), n_ev, 10, torch)
         fp8_ms, pack8_ms = sum(t_fp8) / len(t_fp8), sum(t_pack8) / len(t_pack8)
@@ -335,30 +340,32 @@ def main():
     # cold-cache legs: a 1 GiB buffer is read before every call, so neither the 256 MB MALL nor the
     # L2s hold X, W or the packed operand when the call starts (the hot legs run back to back). The
     # flush reads rather than writes: dirty lines would be written back during the timed call.
-    flush = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-    n_cold = min(n_ev, 30)
-    t_call_cold = event_times(step, n_cold, 3, torch, between=lambda: flush.sum())
-    t_dense_cold = event_times(lambda: rtl.dense_linear(X, W, out=Y, ws=wsd), n_cold, 3, torch,
-                               between=lambda: flush.sum())
-    del flush
     timing = {
         "protocol": "HIP events on the launch stream, per call; hot = back to back, cold = a 1 GiB buffer "
                     "is read before every call; microseconds",
         "hot": {"sparse_linear": summary_us(t_call), "sparsify_pack": summary_us(t_pack),
                 "dense_linear": summary_us(t_dense), "hipblaslt_dense": summary_us(t_blas),
-                "sparse_lora_linear": summary_us(t_lora)},
-        "cold": {"sparse_linear": summary_us(t_call_cold), "dense_linear": summary_us(t_dense_cold),
-                 "speedup_vs_dense_linear": round(sum(t_dense_cold) / sum(t_call_cold), 3)},
+                "sparse_lora_linear": summary_us(t_lora) if t_lora else None},
+        "cold": None,
     }
+    if not args.only_core:
+        flush = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        n_cold = min(n_ev, 30)
+        t_call_cold = event_times(step, n_cold, 3, torch, between=lambda: flush.sum())
+        t_dense_cold = event_times(lambda: rtl.dense_linear(X, W, out=Y, ws=wsd), n_cold, 3, torch,
+                                   between=lambda: flush.sum())
+        del flush
+        timing["cold"] = {"sparse_linear": summary_us(t_call_cold), "dense_linear": summary_us(t_dense_cold),
+                          "speedup_vs_dense_linear": round(sum(t_dense_cold) / sum(t_call_cold), 3)}
     if fp8 is not None:
         fp8["speedup_vs_bf16_sparse_linear"] = round(sum(t_call) / len(t_call) / fp8["ms_per_step"], 3)
     avg = lambda v: sum(v) / len(v)
     call_ms, pack_ms, dense_ms, blas_ms = avg(t_call), avg(t_pack), avg(t_dense), avg(t_blas)
     gemm_ms = call_ms - pack_ms
-    lora_ms = avg(t_lora)
+    lora_ms = avg(t_lora) if t_lora else None
 
     # measured ceilings of the two matrix instructions (register operands only, nothing else running)
-    peaks = {
+    peaks = None if args.only_core else {
         "how": "rtl_diag_matrix_rate: 1024 workgroups x 4 waves issue back-to-back matrix instructions on "
                "register operands; executed TFLOP/s from HIP events; constant operands (all ones) vs N(0,1) operands",
         "smfmac_32x32x32_bf16": {"constant": matrix_rate_probe(rtl, torch, dev, 1, False),
@@ -366,11 +373,11 @@ def main():
         "mfma_32x32x16_bf16": {"constant": matrix_rate_probe(rtl, torch, dev, 0, False),
                                "random": matrix_rate_probe(rtl, torch, dev, 0, True)},
     }
-    gpu_state = gpu_state_under_load(step, torch)
+    gpu_state = None if args.only_core else gpu_state_under_load(step, torch)
 
     executed_flops = float(M) * N * K        # SMFMAC skips the other half of the 2MNK products
     achieved = executed_flops / (gemm_ms * 1e-3) / 1e12
-    measured_peak = peaks["smfmac_32x32x32_bf16"]["random"]["tflops"]
+    measured_peak = peaks["smfmac_32x32x32_bf16"]["random"]["tflops"] if peaks else None
     roofline = {
         "kernel": "gemm_kernel<sparse> (v_smfmac_f32_32x32x32_bf16)",
         "bound": "mfma", "achieved": round(achieved, 1), "peak": DENSE_BF16_PEAK_TFLOPS,
@@ -448,10 +455,11 @@ def main():
         # GEMM alone on the packed operand against the dense GEMMs (the paper's "kernel" speedup)
         "gemm_speedup_vs_dense_linear": round(dense_ms / gemm_ms, 3),
         "gemm_speedup_vs_hipblaslt_dense": round(blas_ms / gemm_ms, 3),
-        "with_lora_r64": {"event_ms_per_call": round(lora_ms, 4), "tflops": round(flops / (lora_ms * 1e-3) / 1e12, 1),
-                          "overhead_vs_sparse_linear": round(lora_ms / call_ms - 1.0, 4),
-                          "speedup_vs_dense_linear": round(dense_ms / lora_ms, 3),
-                          "speedup_vs_best_dense": round(best_dense_ms / lora_ms, 3)},
+        "with_lora_r64": None if lora_ms is None else {
+            "event_ms_per_call": round(lora_ms, 4), "tflops": round(flops / (lora_ms * 1e-3) / 1e12, 1),
+            "overhead_vs_sparse_linear": round(lora_ms / call_ms - 1.0, 4),
+            "speedup_vs_dense_linear": round(dense_ms / lora_ms, 3),
+            "speedup_vs_best_dense": round(best_dense_ms / lora_ms, 3)},
         "with_fp8_e4m3": fp8,
         "timing": timing,
         "measured_peaks": peaks,

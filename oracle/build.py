@@ -17,5 +17,21 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+def build_sanitized() -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host code only, no GPU
+    involved): oracle/librtlynx_oracle_san.so. Load it in a process that preloads the ASan runtime."""
+    lib = os.path.join(HERE, "librtlynx_oracle_san.so")
+    cmd = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-shared", "-fPIC", SRC, "-o", lib, "-lm"]
+    subprocess.run(cmd, check=True)
+    return lib
+
+
+def sanitizer_runtime() -> str:
+    """Path of gcc's libasan.so (to be put first in LD_PRELOAD of the process that loads the build above)."""
+    out = subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True)
+    return os.path.realpath(out.stdout.strip())
+
+
 if __name__ == "__main__":
     print(build(force=True))

@@ -28,6 +28,17 @@ WORKLOADS = {
     "zimage_up": dict(M=4096, K=3840, N=10240, x="laplace"),
     "zimage_down": dict(M=4096, K=10240, N=3840, x="gelu"),
     "zimage_attn": dict(M=4096, K=3840, N=3840, x="laplace"),
+    # non-square images (aspect-ratio generality of the appendix): the same four linears at
+    # 1536x1024 (96 x 64 = 6144 image tokens) and 2304x1024 (144 x 64 = 9216), + 512 text tokens;
+    # 26 and 38 row panels of 256, i.e. ragged tile counts on 256 compute units
+    "ar32_mlp_down": dict(M=6656, K=12288, N=3072, x="gelu"),
+    "ar32_fc1": dict(M=6656, K=3072, N=12288, x="laplace"),
+    "ar32_qkv": dict(M=6656, K=3072, N=9216, x="laplace"),
+    "ar32_out_proj": dict(M=6656, K=3072, N=3072, x="laplace"),
+    "ar94_mlp_down": dict(M=9728, K=12288, N=3072, x="gelu"),
+    "ar94_fc1": dict(M=9728, K=3072, N=12288, x="laplace"),
+    "ar94_qkv": dict(M=9728, K=3072, N=9216, x="laplace"),
+    "ar94_out_proj": dict(M=9728, K=3072, N=3072, x="laplace"),
 }
 SWEEP_BLOCKS = 60
 SWEEP_LAYERS = ("qkv", "out_proj", "fc1", "fc2")
