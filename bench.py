@@ -61,13 +61,38 @@ def _read_number(path):
         return None
 
 
-def gpu_state_under_load(step, torch):
-    """Shader clock and board power WHILE `step` runs back to back. The clock comes from one `rocm-smi`
-    reading taken while this thread keeps the queue full; the power from the amdgpu hwmon file
-    (power1_input / power1_average, microwatts), polled between batches of launches during the same
-    period. Values are null when a source is not readable on the box."""
-    import glob
+SMI_HELPER = r"""
+import json, subprocess, sys
+for line in sys.stdin:                      # one request per line; answers with one JSON line
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        sclk = next((v for k, v in card.items() if k.lower().startswith("sclk")), None)
+        print(json.dumps({"sclk": sclk}), flush=True)
+    except Exception as e:
+        print(json.dumps({"sclk": None, "error": str(e)[:80]}), flush=True)
+"""
+
+
+def start_smi_helper():
+    """A child process that runs `rocm-smi` on request. It is started BEFORE this process touches the
+    GPU (a process that has initialised the GPU must not start other programs), and never touches the
+    GPU itself."""
     import subprocess
+    try:
+        return subprocess.Popen([sys.executable, "-c", SMI_HELPER], stdin=subprocess.PIPE, stdout=subprocess.PIPE,
+                                stderr=subprocess.DEVNULL, text=True)
+    except Exception:
+        return None
+
+
+def gpu_state_under_load(step, torch, smi):
+    """Shader clock and board power WHILE `step` runs back to back. The clock comes from one `rocm-smi`
+    reading that the helper process takes while this process keeps the queue full; the power from the
+    amdgpu hwmon file (power1_average / power1_input, microwatts), polled between batches of launches
+    during the same period. Values are null when a source is not readable on the box."""
+    import glob
+    import select
     out = {"sclk_mhz": None, "power_w": None, "power_cap_w": None, "source": None}
     cap = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
     if cap and _read_number(cap[0]) is not None:
@@ -79,30 +104,32 @@ def gpu_state_under_load(step, torch):
             pw = hits[0]
             break
     p_s = []
-    try:
-        proc = subprocess.Popen(["rocm-smi", "--showclocks", "--json"], stdout=subprocess.PIPE,
-                                stderr=subprocess.DEVNULL, text=True)
-    except Exception:
-        proc = None
-    t_end = time.perf_counter() + (20.0 if proc else 0.25)
-    while time.perf_counter() < t_end and (proc is None or proc.poll() is None):
+    answer = None
+    if smi is not None and smi.poll() is None:
+        try:
+            smi.stdin.write("read\n")
+            smi.stdin.flush()
+        except Exception:
+            smi = None
+    t_end = time.perf_counter() + (20.0 if smi is not None else 0.25)
+    while time.perf_counter() < t_end:
         for _ in range(8):
             step()
         torch.cuda.synchronize()
         if pw:
             p_s.append(_read_number(pw))
+        if smi is not None and select.select([smi.stdout], [], [], 0)[0]:
+            answer = smi.stdout.readline()
+            break
     torch.cuda.synchronize()
     sources = []
-    if proc is not None:
-        if proc.poll() is None:
-            proc.kill()
+    if answer:
         try:
-            card = next(iter(json.loads(proc.communicate()[0]).values()))
-            sclk = next((v for k, v in card.items() if k.lower().startswith("sclk")), None)
-            if sclk is not None:
-                digits = "".join(ch for ch in str(sclk) if ch.isdigit() or ch == ".")
-                out["sclk_mhz"] = float(digits) if digits else None
-                sources.append("sclk: rocm-smi --showclocks, read while the step runs back to back")
+            sclk = json.loads(answer).get("sclk")
+            digits = "".join(ch for ch in str(sclk) if ch.isdigit() or ch == ".")
+            if sclk is not None and digits:
+                out["sclk_mhz"] = float(digits)
+                sources.append("sclk: rocm-smi --showclocks (run by a helper process), read while the step runs back to back")
         except Exception:
             pass
     p_s = [v for v in p_s if v]
@@ -241,6 +268,9 @@ def main():
     ap.add_argument("--dense-layers", default="",
                     help="with --workload sweep: comma-separated layer kinds (qkv,out_proj,fc1,fc2) that stay "
                          "dense in the sparse pass, like the per-model skip lists of the paper's appendix")
+    ap.add_argument("--no-smi", action="store_true",
+                    help="do not start the rocm-smi helper process (required under rocprofv3 --pmc, whose tool "
+                         "library has initialised the GPU before this program starts)")
     ap.add_argument("--only-core", action="store_true",
                     help="time only the step, its pack kernel and the two dense GEMMs (no LoRA, FP8, cold-cache, "
                          "peak-probe or clock legs): the short command the rocprofv3 summaries under profiles/ use")
@@ -252,6 +282,9 @@ def main():
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path has no "
               "multi-GPU part to time", file=sys.stderr)
         sys.exit(2)
+
+    # before anything touches the GPU: the only other program this run ever starts
+    smi = None if (args.no_smi or args.only_core or args.calibrate_copy or args.workload == "sweep") else start_smi_helper()
 
     import torch
     from paper_2605_26632_amd import binding as rtl
@@ -373,7 +406,13 @@ def main():
         "mfma_32x32x16_bf16": {"constant": matrix_rate_probe(rtl, torch, dev, 0, False),
                                "random": matrix_rate_probe(rtl, torch, dev, 0, True)},
     }
-    gpu_state = None if args.only_core else gpu_state_under_load(step, torch)
+    gpu_state = None if args.only_core else gpu_state_under_load(step, torch, smi)
+    if smi is not None:
+        try:
+            smi.stdin.close()
+            smi.wait(timeout=5)
+        except Exception:
+            smi.kill()
 
     executed_flops = float(M) * N * K        # SMFMAC skips the other half of the 2MNK products
     achieved = executed_flops / (gemm_ms * 1e-3) / 1e12

@@ -251,6 +251,12 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
 rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
                                 uint64_t* clocks, float* sink, void* stream);
 
+/* rtl_diag_tile_plan - diagnostic (host arithmetic only, nothing is launched): how the linears cut an
+ * [M, N] output into workgroup tiles. plan (HOST pointer, int64[4]) receives {body tile width (256 or
+ * 192), rows covered by 256-row body tiles, number of body tiles, number of 256 x 128 tail tiles}.
+ * dense != 0 asks for the plan of rtl_dense_linear, else of the sparse linears. */
+rtl_status rtl_diag_tile_plan(int64_t M, int64_t N, int dense, int64_t* plan);
+
 /* Human-readable name of a status code; never NULL. */
 const char* rtl_status_str(rtl_status s);
 /* Library version string, e.g. "rtlynx-gfx950 0.1". */

@@ -397,6 +397,13 @@ rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, i
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
 
+rtl_status rtl_diag_tile_plan(int64_t M, int64_t N, int dense, int64_t* plan) {
+    if (M <= 0 || N <= 0 || M > ((int64_t)1 << 30) || N > ((int64_t)1 << 30)) return RTL_ERR_SHAPE;
+    if (!plan) return RTL_ERR_NULL;
+    rtl::tile_plan(M, N, dense != 0, plan);
+    return RTL_OK;
+}
+
 size_t rtl_dense_linear_workspace(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
     return rtl::gemm_workspace_bytes(false, M, N, K);

@@ -37,7 +37,9 @@
 // In bytes this is the bf16 geometry (16-byte A chunk, two 16-byte B chunks at the same chunk
 // indices), so a stage simply covers 128 dense k instead of 64 and the kernel differs only in the
 // instruction and in the metadata record (16 bytes per row and stage, one 32-bit word per sub-step).
+#include <mutex>
 #include <type_traits>
+#include <vector>
 #include "rtl_internal.h"
 
 namespace rtl {
@@ -141,13 +143,13 @@ __device__ __forceinline__ void unswz4(int p, int& row, int& c) {
 }
 
 // Tile order: consecutive workgroup ids land on different XCDs (round robin), so ids are first
-// regrouped per XCD, then walked in groups of 8 tile-rows so that the ~32 tiles an XCD runs at a
-// time share few activation and weight panels in its L2.
-__device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, int& pm, int& pn) {
-    const int nblk = tiles_m * tiles_n;
-    const int q = nblk / 8, r = nblk % 8;
-    const int xcd = pid % 8, local = pid / 8;
-    const int t = (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + local;
+// regrouped per XCD (XCD x works through a contiguous share of the tile list), and the list walks
+// the tile grid in groups of 8 tile-rows so that the ~32 tiles an XCD runs at a time share few
+// activation and weight panels in its L2.
+__device__ __forceinline__ int xcd_share_start(int n, int xcd) {   // first list index of XCD xcd's share of n tiles
+    return xcd * (n / 8) + min(xcd, n % 8);
+}
+__device__ __forceinline__ void tile_walk(int t, int tiles_m, int tiles_n, int& pm, int& pn) {
     constexpr int GM = 8;
     const int per_group = GM * tiles_n;
     const int group = t / per_group;
@@ -159,9 +161,11 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
 
 // MODE 0: plain linear. MODE 1 (sparse only): LoRA tail, the accumulators also receive T L_A^T before
 // the epilogue. MODE 2: split contraction, grid.y K ranges, fp32 partial tiles instead of Y.
+// `tile`: index of this workgroup's output tile in the walk of the (M / BM) x (N / BN) tile grid;
+// `pid_y`: K range of a split contraction (MODE 2).
 template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
           bool D64 = false>
-__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile, const int pid_y) {
     static_assert(!D64 || (!SPARSE && MODE != 1), "64-k stages: dense kernels only");
     static_assert(MODE == 0 || (MODE == 1 && SPARSE) || (MODE == 2 && !SPARSE), "mode/operand combination");
     static_assert(!FP8 || (SPARSE && MODE == 0), "FP8 operands: plain sparse kernel only");
@@ -198,16 +202,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     int pm, pn;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, pm, pn);
+    tile_walk(tile, tiles_m, tiles_n, pm, pn);
     const int64_t m0 = (int64_t)pm * BM, n0 = (int64_t)pn * BN;
     int KT = (int)(a.K / KSTAGE);
     int kt_first = 0;                                  // first stage of this workgroup's K range
     if constexpr (MODE == 2) {
         const int per = (KT + a.splits - 1) / a.splits;
-        kt_first = (int)blockIdx.y * per;
+        kt_first = pid_y * per;
         KT = max(0, min(per, KT - kt_first));
         if (KT <= 0) {   // cannot happen for the range counts the launcher picks; stay defined anyway
-            float* out = a.partials + (int64_t)blockIdx.y * a.M * a.N;
+            float* out = a.partials + (int64_t)pid_y * a.M * a.N;
             for (int e = tid; e < BM * BN; e += NW * 64) {
                 const int64_t row = m0 + e / BN, col = n0 + e % BN;
                 if (row < a.M && col < a.N) out[row * a.N + col] = 0.f;
@@ -221,7 +225,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     // wave-uniform bases of this tile's three streams, already advanced to the first stage
     // Sparse A is the k-major value buffer: 64 bytes per row and stage, the rows of a stage
     // contiguous, so the tile's stage is one 16 KiB run; dense A is row-major X.
-    const int64_t rows_pad = (a.M + 255) / 256 * 256;
+    const int64_t rows_pad = a.rows_pad;    // rows per k block of the k-major operand (whole activation)
     const int64_t a_stride = SPARSE ? rows_pad * 64 : (int64_t)(A_ELEMS * ESZ);   // bytes between stages
     const uint8_t* base_a = SPARSE
         ? static_cast<const uint8_t*>(a.A) + m0 * 64 + (int64_t)kt_first * a_stride
@@ -537,7 +541,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
 
     if constexpr (MODE == 2) {
         // ---- split contraction: fp32 partial tile of this K range, no epilogue arithmetic ----
-        float* out = a.partials + (int64_t)blockIdx.y * a.M * a.N;
+        float* out = a.partials + (int64_t)pid_y * a.M * a.N;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int64_t col = n0 + wn * WTN + j * 32 + li;
@@ -574,7 +578,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
         constexpr int T_LOADS = BM * 128 / 1024, LA_LOADS = BN * 128 / 1024;   // rows of 64 bf16
         static_assert(T_LOADS % NW == 0 && LA_LOADS % NW == 0, "rank tiles must divide over the waves");
         static_assert((2 * BM + BN) * 128 <= L::kTotal, "rank tiles fit in the ring");
-        const int64_t plane = a.M * kLoraRank;          // T is two bf16 planes: hi, lo
+        const int64_t plane = a.t_plane;                // T is two bf16 planes: hi, lo
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -726,9 +730,51 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const Gemm
     }
 }
 
+// One tile shape per launch (used for the split contraction of the LoRA down-projection).
+template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
+          bool D64 = false>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
+    const int tiles = (int)(((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN));
+    gemm_tile<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>(
+        a, xcd_share_start(tiles, (int)blockIdx.x % 8) + (int)blockIdx.x / 8, (int)blockIdx.y);
+}
+
+// Two tile shapes in one launch (the "block-parallel" balancing of the method section's kernel
+// paragraph, done with tile shapes instead of split contractions): rows [0, m_split) of the output
+// are cut into 256 x BN body tiles, rows [m_split, M) into 256 x 128 tail tiles. Uniform tiles
+// leave the chip's last round of workgroups mostly empty for many layer shapes (e.g. 792 tiles on
+// 256 compute units: 3.09 rounds cost 4); smaller tiles at the end fill that round at 0.6 of a
+// body tile's time. Every XCD works through its share of the body tiles first, then its share of
+// the tail tiles (workgroups are dispatched in id order). tail_tiles == 0: a plain one-shape launch.
+constexpr int kTailBN = 128;
+template <bool SPARSE, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false, bool D64 = false>
+__global__ __launch_bounds__(512) void gemm_mixed_kernel(const GemmArgs a) {
+    static_assert(WAVES_M * WAVES_N == 8, "both tile shapes run with eight waves");
+    const int xcd = (int)blockIdx.x % 8, local = (int)blockIdx.x / 8;
+    const int nb = a.body_tiles, nt = a.tail_tiles;
+    const int nb_x = nb / 8 + (xcd < nb % 8);
+    if (local < nb_x) {
+        GemmArgs b = a;
+        if (nt > 0) b.M = a.m_split;
+        gemm_tile<SPARSE, 256, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>(b, xcd_share_start(nb, xcd) + local, 0);
+    } else {
+        // the tail region as a problem of its own: same operands, shifted by m_split rows
+        constexpr int ESZ = FP8 ? 1 : 2;
+        GemmArgs t = a;
+        t.M = a.M - a.m_split;
+        t.A = static_cast<const uint8_t*>(a.A) + (SPARSE ? a.m_split * 64 : a.m_split * a.lda * ESZ);
+        if constexpr (SPARSE) t.meta = a.meta + a.m_split * (FP8 ? 16 : 8);
+        t.Y = a.Y + a.m_split * a.ldy;
+        if (a.row_scale) t.row_scale = a.row_scale + a.m_split;
+        if constexpr (MODE == 1) t.T = a.T + a.m_split * kLoraRank;
+        const int idx = xcd_share_start(nb + nt, xcd) - xcd_share_start(nb, xcd) + (local - nb_x);
+        gemm_tile<SPARSE, 256, kTailBN, 2, 4, STAGES, MODE, FP8, D64>(t, idx, 0);
+    }
+}
+
 // The tile loops need more dynamic LDS than the default limit of a launch: the limit is raised once
-// per kernel by prepare_cfg (called for every configuration from prepare_gemm_kernels, i.e. from
-// rtl_init or from the first entry-point call on a device), never from a launch, so that launches
+// per kernel by the prepare functions (called for every configuration from prepare_gemm_kernels, i.e.
+// from rtl_init or from the first entry-point call on a device), never from a launch, so that launches
 // consist of the kernel node only and can be recorded into a HIP graph.
 template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
           bool D64 = false>
@@ -750,6 +796,23 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <bool SPARSE, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false, bool D64 = false>
+struct Mixed {
+    using LB = Smem<SPARSE, 256, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
+    using LT = Smem<SPARSE, 256, kTailBN, STAGES, 2, 4, FP8, D64>;
+    static constexpr int kLds = LB::kTotal > LT::kTotal ? LB::kTotal : LT::kTotal;
+    static hipError_t prepare() {
+        auto kern = gemm_mixed_kernel<SPARSE, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    }
+    // a.m_split, a.body_tiles and a.tail_tiles come from the planner
+    static hipError_t launch(const GemmArgs& a, hipStream_t stream) {
+        auto kern = gemm_mixed_kernel<SPARSE, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(a.body_tiles + a.tail_tiles)), dim3(512), kLds, stream, a);
+        return hipGetLastError();
+    }
+};
+
 // T[m, r] = sum over the K ranges, in range order, of the fp32 partials, stored as two bf16 planes
 // hi = bf16(T), lo = bf16(T - hi): the matrix unit takes bf16 operands, and the pair keeps 16
 // significant bits so the residual is as accurate as the fp32-accumulated sparse product.
@@ -768,52 +831,124 @@ __global__ __launch_bounds__(256) void lora_reduce_kernel(const float* __restric
 
 size_t gemm_workspace_bytes(bool, int64_t, int64_t, int64_t) { return 0; }
 
-// Tile choice for the sparse kernel. The main loop is bound by the rate at which a CU can pull
-// operand stages out of L2, so a tile costs about (bytes per stage) and a launch costs
-// ceil(tiles / CUs) rounds of that: 256x256 moves 51 KB per stage, 256x192 moves 43 KB but
-// yields a third more tiles, which pays when it turns a 3/4-full round into a full one.
-// (The dense kernel moves 32 and 28 KB per stage of half the depth.)
-static bool prefer_192(int64_t M, int64_t N, int64_t kb256 = 51, int64_t kb192 = 43) {
-    constexpr int64_t kCUs = 256;
+// ---- tile plan ---------------------------------------------------------------------------------
+// A launch cuts rows [0, m_split) of the output into 256 x BN body tiles (BN = 256 or 192) and the
+// remaining rows into 256 x 128 tail tiles. The main loop is bound by the rate at which a CU can pull
+// operand stages out of L2, so a tile's time goes with its bytes per stage: 256x256 moves 51 KB,
+// 256x192 43 KB (dense kernel: 64 and 56 KB per 64-k stage); a 256x128 tile was measured at 0.60 to
+// 0.66 of a 256x256 tile. The plan is the (BN, m_split) whose simulated schedule ends first: per XCD
+// (32 compute units, one workgroup each), workgroups in id order, each to the unit that frees first.
+struct TilePlan {
+    bool use_192;
+    int64_t m_split;     // rows covered by body tiles (a multiple of 256, or M when there is no tail)
+    int body_tiles, tail_tiles;
+};
+
+static double simulate_schedule(int64_t nb, int64_t nt, double cb, double ct) {
+    double worst = 0.0;
+    for (int x = 0; x < 8; ++x) {
+        const int64_t tot = nb + nt;
+        const int64_t nbx = nb / 8 + (x < nb % 8), cx = tot / 8 + (x < tot % 8);
+        double unit[32] = {0};
+        for (int64_t i = 0; i < cx; ++i) {
+            int best = 0;
+            for (int u = 1; u < 32; ++u)
+                if (unit[u] < unit[best]) best = u;
+            unit[best] += i < nbx ? cb : ct;
+        }
+        for (int u = 0; u < 32; ++u) worst = unit[u] > worst ? unit[u] : worst;
+    }
+    return worst;
+}
+
+static TilePlan make_plan(int64_t M, int64_t N, bool dense) {
+    const double c256 = dense ? 64 : 51, c192 = dense ? 56 : 43, c128 = 0.64 * c256;
     const int64_t tm = (M + 255) / 256;
-    const int64_t t256 = tm * ((N + 255) / 256), t192 = tm * ((N + 191) / 192);
-    const int64_t c256 = (t256 + kCUs - 1) / kCUs * kb256, c192 = (t192 + kCUs - 1) / kCUs * kb192;
-    return c192 < c256;
+    const int64_t n256 = (N + 255) / 256, n192 = (N + 191) / 192, n128 = (N + kTailBN - 1) / kTailBN;
+    TilePlan best{false, M, (int)(tm * n256), 0};
+    double best_cost = simulate_schedule(tm * n256, 0, c256, c128);
+    auto consider = [&](bool use_192, int64_t p) {
+        if (p < 0 || p > tm) return;
+        const int64_t nb = p * (use_192 ? n192 : n256), nt = (tm - p) * n128;
+        double cost = simulate_schedule(nb, nt, use_192 ? c192 : c256, c128);
+        if (nt > 0) cost *= 1.03;          // a tail has to pay for itself
+        if (cost < best_cost - 1e-9) {
+            best_cost = cost;
+            best = TilePlan{use_192, p == tm ? M : p * 256, (int)nb, (int)nt};
+        }
+    };
+    consider(true, tm);
+    // body sizes that fill whole rounds of the chip, and a few panels around them
+    for (int use_192 = 0; use_192 < 2; ++use_192) {
+        const int64_t tn = use_192 ? n192 : n256;
+        const int64_t rounds = tm * tn / 256;
+        for (int64_t r = rounds; r >= rounds - 1 && r >= 0; --r)
+            for (int64_t d = -2; d <= 1; ++d) consider(use_192 != 0, r * 256 / tn + d);
+    }
+    return best;
+}
+
+// Plans are cached per (M, N, kind): the simulation costs tens of microseconds on the host.
+static TilePlan plan_for(int64_t M, int64_t N, bool dense) {
+    struct Entry { int64_t M, N; bool dense; TilePlan plan; };
+    static std::mutex mu;
+    static std::vector<Entry> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Entry& e : cache)
+        if (e.M == M && e.N == N && e.dense == dense) return e.plan;
+    const TilePlan p = make_plan(M, N, dense);
+    if (cache.size() < 4096) cache.push_back(Entry{M, N, dense, p});
+    return p;
+}
+
+void tile_plan(int64_t M, int64_t N, bool dense, int64_t out[4]) {
+    const TilePlan p = plan_for(M, N, dense);
+    out[0] = p.use_192 ? 192 : 256;
+    out[1] = p.m_split;
+    out[2] = p.body_tiles;
+    out[3] = p.tail_tiles;
 }
 
 // Every configuration launch_gemm and launch_lora_down can pick.
 hipError_t prepare_gemm_kernels() {
     hipError_t e = hipSuccess;
     auto run = [&](hipError_t r) { if (e == hipSuccess) e = r; };
-    run(prepare_cfg<true, 256, 192, 4, 2, 3, 0, true>());
-    run(prepare_cfg<true, 256, 256, 2, 4, 3, 0, true>());
-    run(prepare_cfg<true, 256, 192, 4, 2, 3, 1>());
-    run(prepare_cfg<true, 256, 192, 4, 2, 3>());
-    run(prepare_cfg<true, 256, 256, 2, 4, 3, 1>());
-    run(prepare_cfg<true, 256, 256, 2, 4, 3>());
-    run(prepare_cfg<false, 256, 192, 4, 2, 2, 0, false, true>());
-    run(prepare_cfg<false, 256, 256, 2, 4, 2, 0, false, true>());
+    run(Mixed<true, 192, 4, 2, 3, 0, true>::prepare());
+    run(Mixed<true, 256, 2, 4, 3, 0, true>::prepare());
+    run(Mixed<true, 192, 4, 2, 3, 1>::prepare());
+    run(Mixed<true, 192, 4, 2, 3>::prepare());
+    run(Mixed<true, 256, 2, 4, 3, 1>::prepare());
+    run(Mixed<true, 256, 2, 4, 3>::prepare());
+    run(Mixed<false, 192, 4, 2, 2, 0, false, true>::prepare());
+    run(Mixed<false, 256, 2, 4, 2, 0, false, true>::prepare());
     run(prepare_cfg<false, 128, 64, 4, 1, 4, 2, false, true>());
     return e;
 }
 
-hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream) {
+hipError_t launch_gemm(bool sparse, const GemmArgs& a_in, hipStream_t stream) {
+    GemmArgs a = a_in;
+    const TilePlan plan = plan_for(a.M, a.N, !sparse);
+    a.m_split = plan.m_split;
+    a.body_tiles = plan.body_tiles;
+    a.tail_tiles = plan.tail_tiles;
+    a.rows_pad = kmajor_rows(a.M);
+    a.t_plane = a.M * kLoraRank;
     if (sparse && a.fp8) {
-        if (prefer_192(a.M, a.N)) return launch_cfg<true, 256, 192, 4, 2, 3, 0, true>(a, stream);
-        return launch_cfg<true, 256, 256, 2, 4, 3, 0, true>(a, stream);
+        if (plan.use_192) return Mixed<true, 192, 4, 2, 3, 0, true>::launch(a, stream);
+        return Mixed<true, 256, 2, 4, 3, 0, true>::launch(a, stream);
     }
     if (sparse) {
         const bool lora = a.T != nullptr;
-        if (prefer_192(a.M, a.N)) {
-            if (lora) return launch_cfg<true, 256, 192, 4, 2, 3, 1>(a, stream);
-            return launch_cfg<true, 256, 192, 4, 2, 3>(a, stream);
+        if (plan.use_192) {
+            if (lora) return Mixed<true, 192, 4, 2, 3, 1>::launch(a, stream);
+            return Mixed<true, 192, 4, 2, 3>::launch(a, stream);
         }
-        if (lora) return launch_cfg<true, 256, 256, 2, 4, 3, 1>(a, stream);
-        return launch_cfg<true, 256, 256, 2, 4, 3>(a, stream);
+        if (lora) return Mixed<true, 256, 2, 4, 3, 1>::launch(a, stream);
+        return Mixed<true, 256, 2, 4, 3>::launch(a, stream);
     }
     // dense: stages of 64 k (whole-line requests on the row-major operands), ring of two
-    if (prefer_192(a.M, a.N, 64, 56)) return launch_cfg<false, 256, 192, 4, 2, 2, 0, false, true>(a, stream);
-    return launch_cfg<false, 256, 256, 2, 4, 2, 0, false, true>(a, stream);
+    if (plan.use_192) return Mixed<false, 192, 4, 2, 2, 0, false, true>::launch(a, stream);
+    return Mixed<false, 256, 2, 4, 2, 0, false, true>::launch(a, stream);
 }
 
 // ---- LoRA down-projection: a skinny product (N = 64) bound by reading X once. 128-row tiles times

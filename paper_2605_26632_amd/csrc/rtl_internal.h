@@ -67,6 +67,11 @@ struct GemmArgs {
     const uint16_t* T;      // nullable: X L_B^T as two bf16 planes (hi, lo), [2][M,64]
     const uint16_t* LA;     // L_A bf16 [N,64] (ldla)
     int64_t ldla;
+    // filled in by launch_gemm (tile plan and strides of the whole problem):
+    int64_t rows_pad;       // sparse: rows per k block of the k-major operand, kmajor_rows(M of the whole activation)
+    int64_t t_plane;        // LoRA: elements between the hi and lo planes of T (M of the whole activation * 64)
+    int64_t m_split;        // rows [0, m_split) are cut into body tiles, rows [m_split, M) into 256 x 128 tail tiles
+    int body_tiles, tail_tiles;
     int splits;             // split contraction: number of K ranges (grid.y)
     bool fp8;               // sparse only: E4M3 operands, K % 128 == 0, 16-byte metadata records
 };
@@ -77,6 +82,9 @@ size_t gemm_workspace_bytes(bool sparse, int64_t M, int64_t N, int64_t K);
 hipError_t prepare_gemm_kernels();
 hipError_t prepare_pack_kernels();
 hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream);
+// The tile plan launch_gemm uses for an [M, N] output: out = {body tile width (256 or 192), rows covered
+// by body tiles, number of body tiles, number of 256 x 128 tail tiles}. Host arithmetic only.
+void tile_plan(int64_t M, int64_t N, bool dense, int64_t out[4]);
 
 // LoRA down-projection T = X L_B^T ([2][M,64] bf16 hi/lo planes): split-K partial products +
 // ordered reduction.

@@ -134,3 +134,28 @@ def test_fp8_entry_points_reject_bad_arguments():
     assert lin(M=0) == 0
     # half the value bytes of the bf16 workspace, same metadata
     assert L.rtl_sparse_linear_fp8_workspace(4096, 3072, 12288, 1) < L.rtl_sparse_linear_workspace(4096, 3072, 12288, 1)
+
+
+def test_tile_plan_covers_the_output_exactly():
+    """Host arithmetic of the launch plan: body tiles (256 x 256 or 256 x 192) on the first rows, 256 x 128
+    tail tiles on the rest; together they cover every output element once, for any shape."""
+    import random
+    rnd = random.Random(5)
+    shapes = [(4096, 3072), (4608, 12288), (16896, 3072), (1, 1), (255, 129), (257, 193), (100003, 40), (40, 70001)]
+    shapes += [(rnd.randint(1, 20000), rnd.randint(1, 20000)) for _ in range(200)]
+    for M, N in shapes:
+        for dense in (False, True):
+            p = rtl.diag_tile_plan(M, N, dense)
+            assert p["body_width"] in (192, 256)
+            tm = (M + 255) // 256
+            rows = p["body_rows"]
+            assert 0 <= rows <= M and (rows % 256 == 0 or rows == M)
+            body_panels = (rows + 255) // 256
+            assert p["body_tiles"] == body_panels * ((N + p["body_width"] - 1) // p["body_width"])
+            assert p["tail_tiles"] == (tm - body_panels) * ((N + 127) // 128)
+            assert p["body_tiles"] + p["tail_tiles"] >= 1
+            if p["tail_tiles"] == 0:
+                assert rows == M
+    assert rtl.lib().rtl_diag_tile_plan(0, 5, 0, None) == 2 and rtl.lib().rtl_diag_tile_plan(5, 5, 0, None) == 1
+    # the headline shape keeps its one-round plan: 256 tiles of 256 x 192, no tail
+    assert rtl.diag_tile_plan(4096, 3072) == dict(body_width=192, body_rows=4096, body_tiles=256, tail_tiles=0)
