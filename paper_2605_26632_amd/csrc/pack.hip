@@ -113,16 +113,17 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
             if constexpr (FP8) {
                 // Same idea one rounding later: t = p * inv is what gets rounded, to 3 mantissa
                 // bits. The fast and the exact p differ by at most 7 units, which the common
-                // multiplication by inv and its own rounding turn into at most 15 units of t, so
-                // the exact sequence runs when a fast t lies within 16 units of an E4M3 rounding
-                // boundary of the normal range (low 20 bits = 0x80000), or falls into the
-                // subnormal range of the format (0 < |t| < 2^-6), where the boundaries sit elsewhere.
+                // multiplication by inv and its own rounding turn into at most 15 units of t, i.e.
+                // less than 2^-19 |t|. The conversion is monotone, so if t (1 - 2^-17) and
+                // t (1 + 2^-17), which bracket the exact t even after their own roundings, give the
+                // same code, the exact t gives it too, wherever the format's boundaries sit
+                // (normal range, subnormal range, saturation: beyond 448 the raw conversion returns
+                // the NaN code on both sides, or differs across the limit and the exact sequence runs).
                 float t0 = p0 * inv, t1 = p1 * inv;
-                const uint32_t b0 = __float_as_uint(t0), b1 = __float_as_uint(t1);
-                const uint32_t w0 = (b0 + 16u) & 0xFFFFFu, w1 = (b1 + 16u) & 0xFFFFFu;
-                const bool near8 = (w0 - 0x80000u < 32u) | (w1 - 0x80000u < 32u);
-                const bool tiny = (((b0 & 0x7FFFFFFFu) - 1u) < 0x3C7FFFFFu) | (((b1 & 0x7FFFFFFFu) - 1u) < 0x3C7FFFFFu);
-                if (near8 | tiny | odd_range) {
+                constexpr float kBelow = 1.0f - 0x1p-17f, kAbove = 1.0f + 0x1p-17f;
+                const uint32_t c_below = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(t0 * kBelow, t1 * kBelow, 0, false);
+                const uint32_t c_above = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(t0 * kAbove, t1 * kAbove, 0, false);
+                if ((c_below != c_above) | odd_range) {
                     s = exact_group_scale(f0, f1, f2, f3, ka, kb, eps);
                     t0 = (s * ka) * inv;
                     t1 = (s * kb) * inv;
