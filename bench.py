@@ -22,7 +22,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per sparse-GEMM launch on the default workload, from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_kernel_sparse_mlp_down.md
 # (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 KiB after calibration against a plain 1 GiB copy).
-GEMM_TRAFFIC_BYTES = {"mlp_down": int((184767 * 2.0 + 24576 * 1.0) * 1024)}
+# Summary: profiles/rtl_sparse_linear_kernels_mlp_down.md.
+GEMM_TRAFFIC_BYTES = {"mlp_down": int((184524 * 2.0 + 24576 * 1.0) * 1024)}
 
 
 X_KIND = {"gelu": "post-GELU", "laplace": "Laplace rows x log-normal channel scales",
@@ -418,7 +419,7 @@ def main():
     achieved = executed_flops / (gemm_ms * 1e-3) / 1e12
     measured_peak = peaks["smfmac_32x32x32_bf16"]["random"]["tflops"] if peaks else None
     roofline = {
-        "kernel": "gemm_kernel<sparse> (v_smfmac_f32_32x32x32_bf16)",
+        "kernel": "gemm_mixed_kernel<sparse> (v_smfmac_f32_32x32x32_bf16), tile plan %s" % (rtl.diag_tile_plan(M, N),),
         "bound": "mfma", "achieved": round(achieved, 1), "peak": DENSE_BF16_PEAK_TFLOPS,
         "unit": "TFLOP/s", "frac": round(achieved / DENSE_BF16_PEAK_TFLOPS, 4),
         "traffic": GEMM_TRAFFIC_BYTES.get(args.workload) if args.comp == "group" else None,
