@@ -279,11 +279,16 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = rtl::launch_lora_down(static_cast<const uint16_t*>(X), ldx,
                                          static_cast<const uint16_t*>(LB), ldlb, M, K,
-                                         reinterpret_cast<float*>(base + p_off), T, s);
+                                         reinterpret_cast<float*>(base + p_off), s);
     if (e != hipSuccess) return RTL_ERR_HIP;
+    // the pack sweep also folds the partials into T (two bf16 planes) on its way
+    rtl::LoraReduce fold;
+    fold.partials = reinterpret_cast<const float*>(base + p_off);
+    fold.splits = rtl::lora_down_splits(M, K);
+    fold.T = T;
     e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr,
                                   base + ws.vals, base + ws.meta, scale,
-                                  reinterpret_cast<float*>(base + ws.pack), s);
+                                  reinterpret_cast<float*>(base + ws.pack), s, fold);
     if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};
     g.A = base + ws.vals;

@@ -813,20 +813,6 @@ struct Mixed {
     }
 };
 
-// T[m, r] = sum over the K ranges, in range order, of the fp32 partials, stored as two bf16 planes
-// hi = bf16(T), lo = bf16(T - hi): the matrix unit takes bf16 operands, and the pair keeps 16
-// significant bits so the residual is as accurate as the fp32-accumulated sparse product.
-__global__ __launch_bounds__(256) void lora_reduce_kernel(const float* __restrict__ partials, int splits,
-                                                          int64_t n, uint16_t* __restrict__ T) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    float acc = 0.f;
-    for (int s = 0; s < splits; ++s) acc += partials[(int64_t)s * n + i];
-    const uint32_t hi = f32_to_bf16_rne(acc);
-    T[i] = (uint16_t)hi;
-    T[n + i] = (uint16_t)f32_to_bf16_rne(acc - __uint_as_float(hi << 16));
-}
-
 }  // namespace
 
 size_t gemm_workspace_bytes(bool, int64_t, int64_t, int64_t) { return 0; }
@@ -972,17 +958,12 @@ size_t lora_down_partial_bytes(int64_t M, int64_t K) {
     return (size_t)lora_down_splits(M, K) * (size_t)M * kLoraRank * sizeof(float);
 }
 hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
-                            int64_t K, float* partials, uint16_t* T, hipStream_t stream) {
+                            int64_t K, float* partials, hipStream_t stream) {
     GemmArgs g{};
     g.A = X; g.W = LB; g.partials = partials;
     g.M = M; g.N = kLoraRank; g.K = K; g.lda = ldx; g.ldw = ldlb; g.ldy = kLoraRank;
     g.splits = lora_down_splits(M, K);
-    hipError_t e = launch_cfg<false, 128, 64, 4, 1, 4, 2, false, true>(g, stream);
-    if (e != hipSuccess) return e;
-    const int64_t n = M * kLoraRank;
-    hipLaunchKernelGGL(lora_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
-                       partials, g.splits, n, T);
-    return hipGetLastError();
+    return launch_cfg<false, 128, 64, 4, 1, 4, 2, false, true>(g, stream);
 }
 
 }  // namespace rtl

@@ -169,13 +169,24 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     const uint16_t* __restrict__ X, int64_t M, int K, int64_t ldx, float eps,
     void* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ vals_km,
     uint8_t* __restrict__ meta_km, int64_t Mpad, float* __restrict__ scale,
-    float* __restrict__ rowsums, const float* __restrict__ x_scale, int parts) {
+    float* __restrict__ rowsums, const float* __restrict__ x_scale, int parts, LoraReduce lora) {
     const int lane = threadIdx.x & 63;
     // `parts` waves share a row (NONE / GROUP only: nothing is summed along the row), each taking a
     // run of whole 512-element steps; short rows then still give every SIMD enough waves in flight.
     const int64_t gw = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t row = gw / parts;
     if (row >= M) return;  // whole wave leaves together
+    // Side job for the LoRA branch (Alg. 1 "Y_r <- X (L_A L_B)^T" evaluated as (X L_B^T) L_A^T): the
+    // first wave of a row folds the row's split-contraction partials of T = X L_B^T in range order and
+    // stores T as two bf16 planes, hi = bf16(T), lo = bf16(T - hi) (the matrix unit takes bf16 operands;
+    // the pair keeps 16 significant bits). 64 values per row: one per lane.
+    if (lora.T && gw % parts == 0) {
+        float acc = 0.f;
+        for (int sp = 0; sp < lora.splits; ++sp) acc += lora.partials[((int64_t)sp * M + row) * 64 + lane];
+        const uint32_t hi = f32_to_bf16_rne(acc);
+        lora.T[row * 64 + lane] = (uint16_t)hi;
+        lora.T[(M + row) * 64 + lane] = (uint16_t)f32_to_bf16_rne(acc - __uint_as_float(hi << 16));
+    }
     const int span = ((K + parts - 1) / parts + 511) / 512 * 512;
     const int kbeg = (int)(gw % parts) * span;
     const int kend = min(K, kbeg + span);
@@ -349,7 +360,7 @@ template <bool FP8>
 static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                   float eps, void* vals, uint8_t* meta, uint8_t* vals_km, uint8_t* meta_km,
                                   float* scale, float* rowsums, const float* x_scale, float* fused_scale,
-                                  hipStream_t stream) {
+                                  LoraReduce lora, hipStream_t stream) {
     const int64_t Mpad = kmajor_rows(M);
     // Waves per row: two once each still has a full unrolled trip of work (measured: 34 -> 31 us at
     // [4096,12288], 141 -> 131 us at [16896,12288], no change at K = 3072; four or more waves per row
@@ -361,19 +372,19 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
     switch (comp) {
         case RTL_COMP_NONE:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_NONE, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
             break;
         case RTL_COMP_GROUP:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_GROUP, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
             break;
         case RTL_COMP_ROW:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_ROW, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
             break;
         case RTL_COMP_TENSOR:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_TENSOR, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
             hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps,
                                scale, x_scale, fused_scale);
             break;
@@ -383,9 +394,10 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
 
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                 float eps, uint16_t* vals, uint8_t* meta, uint8_t* vals_km,
-                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream) {
+                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream,
+                                LoraReduce lora) {
     return launch_pack_any<false>(X, M, K, ldx, comp, eps, vals, meta, vals_km, meta_km, scale, rowsums,
-                                  nullptr, nullptr, stream);
+                                  nullptr, nullptr, lora, stream);
 }
 
 hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
@@ -393,7 +405,7 @@ hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int
                                     uint8_t* vals_km, uint8_t* meta_km, float* scale, float* rowsums,
                                     float* fused_scale, hipStream_t stream) {
     return launch_pack_any<true>(X, M, K, ldx, comp, eps, vals8, meta, vals_km, meta_km, scale, rowsums,
-                                 x_scale, fused_scale, stream);
+                                 x_scale, fused_scale, LoraReduce{}, stream);
 }
 
 hipError_t launch_quantize_fp8(const uint16_t* W, int64_t rows, int64_t cols, int64_t ld, uint8_t* Wq,

@@ -31,9 +31,17 @@ inline size_t kmajor_val_bytes(int64_t M, int64_t K, size_t val_bytes) {
 // Launches the select/compensate/compress sweep. The canonical outputs (`vals`, `meta`) and the
 // k-major ones (`vals_km`, `meta_km`, need K % 64 == 0) are each optional; `rowsums` ([M][2] fp32)
 // is only touched for RTL_COMP_TENSOR. Returns the HIP launch status.
+// `lora` (optional side job of the sweep, LoRA branch only): fold the `splits` fp32 partial planes
+// [splits][M][64] of T = X L_B^T in range order and store T as two bf16 planes [2][M][64] (hi, lo).
+struct LoraReduce {
+    const float* partials = nullptr;
+    int splits = 0;
+    uint16_t* T = nullptr;
+};
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                 float eps, uint16_t* vals, uint8_t* meta, uint8_t* vals_km,
-                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream);
+                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream,
+                                LoraReduce lora = LoraReduce{});
 // FP8 form (implementation details, "orthogonal validation with FP8 quantization"): kept values
 // leave as E4M3 codes of (s * x) / x_scale[0] (vals8 [M,K/2] bytes); `meta_km` then uses the 16-byte
 // records and `vals_km` 128-k blocks (need K % 128 == 0). `fused_scale` (nullable, [1]) receives
@@ -86,13 +94,14 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream);
 // by body tiles, number of body tiles, number of 256 x 128 tail tiles}. Host arithmetic only.
 void tile_plan(int64_t M, int64_t N, bool dense, int64_t out[4]);
 
-// LoRA down-projection T = X L_B^T ([2][M,64] bf16 hi/lo planes): split-K partial products +
-// ordered reduction.
+// LoRA down-projection, first half: split-K partial products of T = X L_B^T into `partials`
+// ([splits][M][64] fp32, splits = lora_down_splits(M, K)). The ordered reduction to the bf16 hi/lo
+// planes rides on the pack sweep that follows (LoraReduce above).
 constexpr int kLoraRank = 64;
 int lora_down_splits(int64_t M, int64_t K);
 size_t lora_down_partial_bytes(int64_t M, int64_t K);
 hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
-                            int64_t K, float* partials, uint16_t* T, hipStream_t stream);
+                            int64_t K, float* partials, hipStream_t stream);
 
 // ---- diagnostics (diag.hip) -------------------------------------------------------------------
 // Issue-rate probe: `blocks` workgroups of four waves, each wave issuing 4 * iters matrix
