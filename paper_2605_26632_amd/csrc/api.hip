@@ -138,7 +138,7 @@ static rtl_status check_linear(const void* A, const void* W, const void* Y, int6
     // the tile loop addresses the 256 rows of a tile with 32-bit byte offsets from the tile's base
     if (lda > ((int64_t)1 << 22) || ldw > ((int64_t)1 << 22)) return RTL_ERR_SHAPE;
     // one workgroup per output tile, numbered with 32-bit integers (far beyond what fits in memory)
-    if (((M + 255) / 256) * ((N + 191) / 192) >= ((int64_t)1 << 31)) return RTL_ERR_SHAPE;
+    if (((M + 255) / 256) * ((N + 127) / 128) >= ((int64_t)1 << 31)) return RTL_ERR_SHAPE;
     if (M == 0 || N == 0) return RTL_OK;
     if (!A || !W || !Y) return RTL_ERR_NULL;
     if (lda % 8 != 0 || ldw % ldw_granule != 0 || !aligned(A, 16) || !aligned(W, 16) || !aligned(Y, 2))

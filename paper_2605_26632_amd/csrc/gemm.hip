@@ -851,6 +851,12 @@ static TilePlan make_plan(int64_t M, int64_t N, bool dense) {
     const double c256 = dense ? 64 : 51, c192 = dense ? 56 : 43, c128 = 0.64 * c256;
     const int64_t tm = (M + 255) / 256;
     const int64_t n256 = (N + 255) / 256, n192 = (N + 191) / 192, n128 = (N + kTailBN - 1) / kTailBN;
+    if (tm * n128 > (int64_t)1 << 16) {
+        // very large grids: many rounds, the last one no longer matters; pick the cheaper uniform shape
+        // by rounds x bytes per stage and skip the simulation (it is linear in the number of tiles)
+        const double r256 = (double)((tm * n256 + 255) / 256) * c256, r192 = (double)((tm * n192 + 255) / 256) * c192;
+        return r192 < r256 ? TilePlan{true, M, (int)(tm * n192), 0} : TilePlan{false, M, (int)(tm * n256), 0};
+    }
     TilePlan best{false, M, (int)(tm * n256), 0};
     double best_cost = simulate_schedule(tm * n256, 0, c256, c128);
     auto consider = [&](bool use_192, int64_t p) {
