@@ -167,6 +167,31 @@ def matrix_rate_probe(rtl, torch, dev, kind, random_operands):
     return {"tflops": round(best[1], 1), "shader_ghz": None if best[2] is None else round(best[2], 3)}
 
 
+def fill_rate_probe(rtl, torch, dev, region_mib):
+    """Measured ceiling of the L2 -> LDS path (rtl_diag_fill_rate): every compute unit streams a region of
+    `region_mib` MiB into LDS with direct-to-LDS loads and nothing else."""
+    region = torch.ones(region_mib << 20, dtype=torch.uint8, device=dev)
+    iters, blocks = 1500, 256
+    best = None
+    for _ in range(4):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        clocks, nbytes = rtl.diag_fill_rate(region, iters, blocks)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b)
+        c = clocks.cpu().tolist()
+        if best is None or ms < best[0]:
+            best = (ms, nbytes, c)
+    ms, nbytes, c = best
+    ghz = c[0] / (c[1] * 10.0) if c[1] > 0 else None
+    return {"region_mib": region_mib, "tb_per_s": round(nbytes / (ms * 1e-3) / 1e12, 2),
+            "gb_per_s_per_cu": round(nbytes / blocks / (ms * 1e-3) / 1e9, 1),
+            "shader_ghz": None if ghz is None else round(ghz, 3),
+            # per clock: the launch's bytes per unit over (event time x the clock the kernel itself measured)
+            "bytes_per_clk_per_cu": None if ghz is None else round(nbytes / blocks / (ms * 1e-3 * ghz * 1e9), 1)}
+
+
 def summary_us(v):
     v = sorted(v)
     return {"mean": round(sum(v) / len(v) * 1e3, 1), "median": round(v[len(v) // 2] * 1e3, 1),
@@ -406,6 +431,10 @@ def main():
                                  "random": matrix_rate_probe(rtl, torch, dev, 1, True)},
         "mfma_32x32x16_bf16": {"constant": matrix_rate_probe(rtl, torch, dev, 0, False),
                                "random": matrix_rate_probe(rtl, torch, dev, 0, True)},
+        "l2_to_lds_fill": {"how": "rtl_diag_fill_rate: 256 workgroups x 8 waves stream a resident region into LDS with "
+                                  "direct-to-LDS 16-byte loads, 8 requests in flight per wave, nothing else running",
+                           "l2_resident": fill_rate_probe(rtl, torch, dev, 3),
+                           "mall_resident": fill_rate_probe(rtl, torch, dev, 96)},
     }
     gpu_state = None if args.only_core else gpu_state_under_load(step, torch, smi)
     if smi is not None:
@@ -415,6 +444,11 @@ def main():
         except Exception:
             smi.kill()
 
+    # operand bytes one compute unit streams into LDS per launch: per stage of 64 k a 256-row tile needs
+    # 256 x 72 B of compressed activation and 128 B per weight row; tiles of the plan spread over 256 units
+    plan = rtl.diag_tile_plan(M, N)
+    stage = lambda bn: 256 * 72 + bn * 128
+    stage_bytes_per_cu = (K // 64) * (plan["body_tiles"] * stage(plan["body_width"]) + plan["tail_tiles"] * stage(128)) / 256.0
     executed_flops = float(M) * N * K        # SMFMAC skips the other half of the 2MNK products
     achieved = executed_flops / (gemm_ms * 1e-3) / 1e12
     measured_peak = peaks["smfmac_32x32x32_bf16"]["random"]["tflops"] if peaks else None
@@ -433,6 +467,14 @@ def main():
         "note": "achieved = executed flops M*N*K per launch / mean launch time (HIP events: whole call minus its pack "
                 "kernel); the same fraction holds for effective 2MNK flops against the 2:4 peak (2x dense)",
         "avg_launch_ms": round(gemm_ms, 4),
+        # the unit that sets the stage rate of the tile loop: the compute unit's L2 -> LDS path
+        "fill_path": None if not peaks else {
+            "tile_loop_gb_per_s_per_cu": round(stage_bytes_per_cu / (gemm_ms * 1e-3) / 1e9, 1),
+            "probe_gb_per_s_per_cu": peaks["l2_to_lds_fill"]["l2_resident"]["gb_per_s_per_cu"],
+            "probe_bytes_per_clk_per_cu": peaks["l2_to_lds_fill"]["l2_resident"]["bytes_per_clk_per_cu"],
+            "note": "bytes a compute unit pulls into LDS per launch (operand stages of its tiles) / launch time, next to "
+                    "what the bare streaming probe reaches at ITS clock (2.4 GHz, nothing else running); at the 1.4 GHz "
+                    "the tile loop holds under matrix load (profiles/shader_clock_under_load.md) it moves ~40 B/clk/CU"},
         "pack_kernel": {"bound": "hbm", "achieved": round(3.125 * M * K / (pack_ms * 1e-3) / 1e9, 1),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": round(3.125 * M * K / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -251,6 +251,17 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
 rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
                                 uint64_t* clocks, float* sink, void* stream);
 
+/* rtl_diag_fill_rate - diagnostic, not a step of the method: measures how fast the compute units can
+ * stream operands from the L2s into LDS with the direct-to-LDS loads the tile loops are built on, with
+ * nothing else running; the stage rate of a tile loop cannot exceed it.
+ *   region    device, region_bytes bytes (>= 1 MiB, a multiple of 8192, 1024-byte aligned), only read.
+ *             A few MiB stay resident in the L2s, up to ~200 MiB in the memory-side cache.
+ *   iters     1 .. 2^24; blocks 1 .. 65536 workgroups of eight waves (256 = one per compute unit).
+ *             Bytes moved per launch: blocks * 8 * iters * 8192.
+ *   clocks    device uint64[2] as for rtl_diag_matrix_rate; sink device float[1], never written. */
+rtl_status rtl_diag_fill_rate(const void* region, size_t region_bytes, int64_t iters, int blocks,
+                              uint64_t* clocks, float* sink, void* stream);
+
 /* rtl_diag_tile_plan - diagnostic (host arithmetic only, nothing is launched): how the linears cut an
  * [M, N] output into workgroup tiles. plan (HOST pointer, int64[4]) receives {body tile width (256 or
  * 192), rows covered by 256-row body tiles, number of body tiles, number of 256 x 128 tail tiles}.

@@ -21,7 +21,7 @@ SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linea
            "rtl_dense_linear_workspace", "rtl_dense_linear",
            "rtl_quantize_fp8", "rtl_sparsify_pack_fp8_workspace", "rtl_sparsify_pack_fp8",
            "rtl_sparse_linear_fp8_workspace", "rtl_sparse_linear_fp8",
-           "rtl_diag_matrix_rate", "rtl_diag_tile_plan", "rtl_init", "rtl_status_str", "rtl_version"]
+           "rtl_diag_matrix_rate", "rtl_diag_fill_rate", "rtl_diag_tile_plan", "rtl_init", "rtl_status_str", "rtl_version"]
 
 _lib = None
 
@@ -76,6 +76,8 @@ def lib():
         L.rtl_sparse_linear_fp8.restype = ci
         L.rtl_diag_matrix_rate.argtypes = [ci, vp, i64, ci, vp, vp, vp]
         L.rtl_diag_matrix_rate.restype = ci
+        L.rtl_diag_fill_rate.argtypes = [vp, sz, i64, ci, vp, vp, vp]
+        L.rtl_diag_fill_rate.restype = ci
         L.rtl_diag_tile_plan.argtypes = [i64, i64, ci, C.POINTER(C.c_int64)]
         L.rtl_diag_tile_plan.restype = ci
         L.rtl_init.argtypes = []
@@ -309,3 +311,15 @@ def diag_tile_plan(M, N, dense=False):
     out = (C.c_int64 * 4)()
     _check(lib().rtl_diag_tile_plan(int(M), int(N), int(bool(dense)), out), "rtl_diag_tile_plan")
     return dict(body_width=int(out[0]), body_rows=int(out[1]), body_tiles=int(out[2]), tail_tiles=int(out[3]))
+
+
+def diag_fill_rate(region, iters, blocks=256):
+    """rtl_diag_fill_rate: enqueue the L2 -> LDS streaming probe on `region` (a uint8 device tensor);
+    returns (clocks int64[2] tensor, bytes moved by the launch)."""
+    _need_cuda(region)
+    nbytes = region.numel() * region.element_size()
+    clocks = torch.zeros(2, dtype=torch.int64, device=region.device)
+    sink = torch.zeros(1, dtype=torch.float32, device=region.device)
+    st = lib().rtl_diag_fill_rate(_p(region), nbytes, int(iters), int(blocks), _p(clocks), _p(sink), _stream())
+    _check(st, "rtl_diag_fill_rate")
+    return clocks, float(blocks) * 8 * iters * 8192

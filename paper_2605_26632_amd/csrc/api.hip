@@ -38,7 +38,8 @@ rtl_status device_ready(void** scratch_out = nullptr) {
             if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
                 d.state = -1;
             } else {
-                if (rtl::prepare_pack_kernels() != hipSuccess || rtl::prepare_gemm_kernels() != hipSuccess)
+                if (rtl::prepare_pack_kernels() != hipSuccess || rtl::prepare_gemm_kernels() != hipSuccess ||
+                    rtl::prepare_diag_kernels() != hipSuccess)
                     return RTL_ERR_HIP;
                 void* ptr = nullptr;
                 if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return RTL_ERR_HIP;
@@ -399,6 +400,19 @@ rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, i
     hipError_t e = rtl::launch_matrix_rate(kind, operands, iters, blocks,
                                            reinterpret_cast<unsigned long long*>(clocks), sink,
                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
+rtl_status rtl_diag_fill_rate(const void* region, size_t region_bytes, int64_t iters, int blocks,
+                              uint64_t* clocks, float* sink, void* stream) {
+    if (iters <= 0 || iters > ((int64_t)1 << 24) || blocks <= 0 || blocks > 65536) return RTL_ERR_SHAPE;
+    if (region_bytes < ((size_t)1 << 20) || region_bytes % 8192 != 0) return RTL_ERR_SHAPE;
+    if (!region || !clocks || !sink) return RTL_ERR_NULL;
+    if (!aligned(region, 1024) || !aligned(clocks, 8) || !aligned(sink, 4)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
+    hipError_t e = rtl::launch_fill_rate(region, region_bytes, iters, blocks,
+                                         reinterpret_cast<unsigned long long*>(clocks), sink,
+                                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
 

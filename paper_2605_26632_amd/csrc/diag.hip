@@ -1,4 +1,5 @@
-// Diagnostics of librtlynx: an issue-rate probe of the matrix instructions the linears are built on.
+// Diagnostics of librtlynx: an issue-rate probe of the matrix instructions the linears are built on,
+// and a probe of the rate at which a compute unit can stream operands from L2 into LDS.
 //
 // Not a step of the method: it measures what the chip sustains when nothing but the matrix
 // instruction runs (operands in registers, no LDS, no memory traffic), so that the achieved rate of
@@ -75,7 +76,58 @@ __global__ __launch_bounds__(256) void matrix_rate_kernel(const uint4* __restric
     if (s == 12345.678f) sink[0] = s;        // keeps the accumulators alive; practically never true
 }
 
+// Fill-rate probe: every workgroup (8 waves) streams `region` (kept small enough to stay in the
+// L2s / the MALL) into its LDS with the same direct-to-LDS 16-byte loads the tile loops use, eight
+// 1 KiB requests in flight per wave, and nothing else. What a compute unit can pull per clock through
+// this path is the ceiling of a tile loop's stage rate.
+__global__ __launch_bounds__(512) void fill_rate_kernel(const uint8_t* __restrict__ region, size_t region_bytes,
+                                                        int64_t iters, unsigned long long* __restrict__ clocks,
+                                                        float* __restrict__ sink) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem + wave * 8192;
+    // a wave walks the region in steps of 8 KiB (8 requests of 1 KiB), starting at its own offset
+    size_t off = (((size_t)blockIdx.x * 8 + wave) * 8192) % region_bytes;
+    unsigned long long c0 = 0, w0 = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        c0 = clock64();
+        w0 = wall_clock64();
+    }
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint8_t* p = region + off + u * 1024 + lane * 16;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(lds0 + u * 1024), "v"(p) : "memory", "m0");
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70 | 8);      // at most 8 requests outstanding: two batches overlap
+        off += (size_t)gridDim.x * 8 * 8192;
+        if (off + 8192 > region_bytes) off %= (region_bytes - 8192 + 1);
+        off &= ~(size_t)1023;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        clocks[0] = clock64() - c0;
+        clocks[1] = wall_clock64() - w0;
+    }
+    __syncthreads();
+    if (smem[threadIdx.x] == 0x5Au && smem[threadIdx.x + 512] == 0xA5u && iters < 0) sink[0] = 1.0f;   // keeps the loads alive
+}
+
 }  // namespace
+
+hipError_t prepare_diag_kernels() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(fill_rate_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+}
+
+hipError_t launch_fill_rate(const void* region, size_t region_bytes, int64_t iters, int blocks,
+                            unsigned long long* clocks, float* sink, hipStream_t stream) {
+    hipLaunchKernelGGL(fill_rate_kernel, dim3((unsigned)blocks), dim3(512), 65536, stream,
+                       static_cast<const uint8_t*>(region), region_bytes, iters, clocks, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
                               unsigned long long* clocks, float* sink, hipStream_t stream) {

@@ -110,5 +110,10 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, 
 // of the first wave.
 hipError_t launch_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
                               unsigned long long* clocks, float* sink, hipStream_t stream);
+// Fill-rate probe: `blocks` workgroups of eight waves stream `region` into LDS with direct-to-LDS
+// loads, 8 KiB per wave and iteration (bytes moved: blocks * 8 * iters * 8192). clocks as above.
+hipError_t prepare_diag_kernels();
+hipError_t launch_fill_rate(const void* region, size_t region_bytes, int64_t iters, int blocks,
+                            unsigned long long* clocks, float* sink, hipStream_t stream);
 
 }  // namespace rtl
