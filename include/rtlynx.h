@@ -254,7 +254,7 @@ rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, i
 /* rtl_diag_fill_rate - diagnostic, not a step of the method: measures how fast the compute units can
  * stream operands from the L2s into LDS with the direct-to-LDS loads the tile loops are built on, with
  * nothing else running; the stage rate of a tile loop cannot exceed it.
- *   region    device, region_bytes bytes (>= 1 MiB, a multiple of 8192, 1024-byte aligned), only read.
+ *   region    device, region_bytes bytes (>= 1 MiB, a multiple of 8192, 16-byte aligned), only read.
  *             A few MiB stay resident in the L2s, up to ~200 MiB in the memory-side cache.
  *   iters     1 .. 2^24; blocks 1 .. 65536 workgroups of eight waves (256 = one per compute unit).
  *             Bytes moved per launch: blocks * 8 * iters * 8192.

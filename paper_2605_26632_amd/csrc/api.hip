@@ -408,7 +408,7 @@ rtl_status rtl_diag_fill_rate(const void* region, size_t region_bytes, int64_t i
     if (iters <= 0 || iters > ((int64_t)1 << 24) || blocks <= 0 || blocks > 65536) return RTL_ERR_SHAPE;
     if (region_bytes < ((size_t)1 << 20) || region_bytes % 8192 != 0) return RTL_ERR_SHAPE;
     if (!region || !clocks || !sink) return RTL_ERR_NULL;
-    if (!aligned(region, 1024) || !aligned(clocks, 8) || !aligned(sink, 4)) return RTL_ERR_ALIGN;
+    if (!aligned(region, 16) || !aligned(clocks, 8) || !aligned(sink, 4)) return RTL_ERR_ALIGN;
     RTL_REQUIRE_DEVICE();
     hipError_t e = rtl::launch_fill_rate(region, region_bytes, iters, blocks,
                                          reinterpret_cast<unsigned long long*>(clocks), sink,

@@ -181,8 +181,17 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     // stores T as two bf16 planes, hi = bf16(T), lo = bf16(T - hi) (the matrix unit takes bf16 operands;
     // the pair keeps 16 significant bits). 64 values per row: one per lane.
     if (lora.T && gw % parts == 0) {
+        // (the loads of up to eight ranges are in flight together; the additions keep the range order)
         float acc = 0.f;
-        for (int sp = 0; sp < lora.splits; ++sp) acc += lora.partials[((int64_t)sp * M + row) * 64 + lane];
+        for (int sp0 = 0; sp0 < lora.splits; sp0 += 8) {
+            float p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                p[u] = sp0 + u < lora.splits ? lora.partials[((int64_t)(sp0 + u) * M + row) * 64 + lane] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (sp0 + u < lora.splits) acc += p[u];
+        }
         const uint32_t hi = f32_to_bf16_rne(acc);
         lora.T[row * 64 + lane] = (uint16_t)hi;
         lora.T[(M + row) * 64 + lane] = (uint16_t)f32_to_bf16_rne(acc - __uint_as_float(hi << 16));
