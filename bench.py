@@ -167,6 +167,16 @@ def matrix_rate_probe(rtl, torch, dev, kind, random_operands):
     return {"tflops": round(best[1], 1), "shader_ghz": None if best[2] is None else round(best[2], 3)}
 
 
+def context_leg(name, fn):
+    """Run a context leg (a figure next to the metric, never the metric itself). A failure there must not
+    cost the run its metric line: it is reported on stderr and as {"error": ...} in the leg's field."""
+    try:
+        return fn()
+    except Exception as e:                      # noqa: BLE001 - reported, not hidden
+        print("bench.py: context leg %s failed: %s: %s" % (name, type(e).__name__, e), file=sys.stderr)
+        return {"error": "%s: %s" % (type(e).__name__, e)}
+
+
 def fill_rate_probe(rtl, torch, dev, region_mib):
     """Measured ceiling of the L2 -> LDS path (rtl_diag_fill_rate): every compute unit streams a region of
     `region_mib` MiB into LDS with direct-to-LDS loads and nothing else."""
@@ -365,14 +375,17 @@ def main():
     t_dense = event_times(lambda: rtl.dense_linear(X, W, out=Y, ws=wsd), n_ev, 10, torch)
     t_blas = event_times(lambda: torch.matmul(X, W.t(), out=Y), n_ev, 10, torch)
     # whole Alg. 1 with its rank-64 LoRA residual (context: the paper's linear-layer figures include it)
-    t_lora = None
+    t_lora, lora_error = None, None
     if not args.only_core:
-        LA, LB = synth.lora(N, K, 64, seed=3, device=dev)
-        wsl = torch.empty(rtl.sparse_lora_linear_workspace(M, N, K, 64, comp) + 256, dtype=torch.uint8, device=dev)
-        t_lora = event_times(lambda: rtl.sparse_lora_linear(X, W, LA, LB, comp=comp, out=Y, ws=wsl), n_ev, 10, torch)
+        def lora_leg():
+            LA, LB = synth.lora(N, K, 64, seed=3, device=dev)
+            wsl = torch.empty(rtl.sparse_lora_linear_workspace(M, N, K, 64, comp) + 256, dtype=torch.uint8, device=dev)
+            return event_times(lambda: rtl.sparse_lora_linear(X, W, LA, LB, comp=comp, out=Y, ws=wsl), n_ev, 10, torch)
+        t_lora = context_leg("with_lora_r64", lora_leg)
+        if isinstance(t_lora, dict):
+            t_lora, lora_error = None, t_lora
     # FP8 composition (W8A8 + 2:4 activation sparsity; context, another precision than `value`)
-    fp8 = None
-    if K % 128 == 0 and not args.only_core:
+    def fp8_leg():
         xs8 = (X.float().abs().max() * (2.0 ** 0.5) / 448.0).reshape(1).to(torch.float32)
         Wq = rtl.quantize_fp8(W)
         ws8 = torch.empty(rtl.sparse_linear_fp8_workspace(M, N, K, comp) + 256, dtype=torch.uint8, device=dev)
@@ -393,6 +406,8 @@ def main():
             fp8["hipblaslt_fp8_dense_ms"] = round(sum(t_d8) / len(t_d8), 4)
         except Exception:          # no FP8 GEMM in this torch build: the context figure stays null
             pass
+        return fp8
+    fp8 = context_leg("with_fp8_e4m3", fp8_leg) if K % 128 == 0 and not args.only_core else None
     # cold-cache legs: a 1 GiB buffer is read before every call, so neither the 256 MB MALL nor the
     # L2s hold X, W or the packed operand when the call starts (the hot legs run back to back). The
     # flush reads rather than writes: dirty lines would be written back during the timed call.
@@ -413,7 +428,7 @@ def main():
         del flush
         timing["cold"] = {"sparse_linear": summary_us(t_call_cold), "dense_linear": summary_us(t_dense_cold),
                           "speedup_vs_dense_linear": round(sum(t_dense_cold) / sum(t_call_cold), 3)}
-    if fp8 is not None:
+    if fp8 is not None and "error" not in fp8:
         fp8["speedup_vs_bf16_sparse_linear"] = round(sum(t_call) / len(t_call) / fp8["ms_per_step"], 3)
     # ---- the timed region: W warm-up steps, then exactly K steps between two synchronisations. It runs
     #      after the context legs above, which have brought the chip to its working clocks and
@@ -439,16 +454,16 @@ def main():
     peaks = None if args.only_core else {
         "how": "rtl_diag_matrix_rate: 1024 workgroups x 4 waves issue back-to-back matrix instructions on "
                "register operands; executed TFLOP/s from HIP events; constant operands (all ones) vs N(0,1) operands",
-        "smfmac_32x32x32_bf16": {"constant": matrix_rate_probe(rtl, torch, dev, 1, False),
-                                 "random": matrix_rate_probe(rtl, torch, dev, 1, True)},
-        "mfma_32x32x16_bf16": {"constant": matrix_rate_probe(rtl, torch, dev, 0, False),
-                               "random": matrix_rate_probe(rtl, torch, dev, 0, True)},
+        "smfmac_32x32x32_bf16": {"constant": context_leg("smfmac constant", lambda: matrix_rate_probe(rtl, torch, dev, 1, False)),
+                                 "random": context_leg("smfmac random", lambda: matrix_rate_probe(rtl, torch, dev, 1, True))},
+        "mfma_32x32x16_bf16": {"constant": context_leg("mfma constant", lambda: matrix_rate_probe(rtl, torch, dev, 0, False)),
+                               "random": context_leg("mfma random", lambda: matrix_rate_probe(rtl, torch, dev, 0, True))},
         "l2_to_lds_fill": {"how": "rtl_diag_fill_rate: 256 workgroups x 8 waves stream a resident region into LDS with "
                                   "direct-to-LDS 16-byte loads, 8 requests in flight per wave, nothing else running",
-                           "l2_resident": fill_rate_probe(rtl, torch, dev, 3),
-                           "mall_resident": fill_rate_probe(rtl, torch, dev, 96)},
+                           "l2_resident": context_leg("fill l2", lambda: fill_rate_probe(rtl, torch, dev, 3)),
+                           "mall_resident": context_leg("fill mall", lambda: fill_rate_probe(rtl, torch, dev, 96))},
     }
-    gpu_state = None if args.only_core else gpu_state_under_load(step, torch, smi)
+    gpu_state = None if args.only_core else context_leg("gpu state", lambda: gpu_state_under_load(step, torch, smi))
     if smi is not None:
         try:
             smi.stdin.close()
@@ -463,7 +478,8 @@ def main():
     stage_bytes_per_cu = (K // 64) * (plan["body_tiles"] * stage(plan["body_width"]) + plan["tail_tiles"] * stage(128)) / 256.0
     executed_flops = float(M) * N * K        # SMFMAC skips the other half of the 2MNK products
     achieved = executed_flops / (gemm_ms * 1e-3) / 1e12
-    measured_peak = peaks["smfmac_32x32x32_bf16"]["random"]["tflops"] if peaks else None
+    measured_peak = peaks["smfmac_32x32x32_bf16"]["random"].get("tflops") if peaks else None
+    fill_probe = peaks["l2_to_lds_fill"]["l2_resident"] if peaks else {}
     roofline = {
         "kernel": "gemm_mixed_kernel<sparse> (v_smfmac_f32_32x32x32_bf16), tile plan %s" % (rtl.diag_tile_plan(M, N),),
         "bound": "mfma", "achieved": round(achieved, 1), "peak": DENSE_BF16_PEAK_TFLOPS,
@@ -482,8 +498,8 @@ def main():
         # the unit that sets the stage rate of the tile loop: the compute unit's L2 -> LDS path
         "fill_path": None if not peaks else {
             "tile_loop_gb_per_s_per_cu": round(stage_bytes_per_cu / (gemm_ms * 1e-3) / 1e9, 1),
-            "probe_gb_per_s_per_cu": peaks["l2_to_lds_fill"]["l2_resident"]["gb_per_s_per_cu"],
-            "probe_bytes_per_clk_per_cu": peaks["l2_to_lds_fill"]["l2_resident"]["bytes_per_clk_per_cu"],
+            "probe_gb_per_s_per_cu": fill_probe.get("gb_per_s_per_cu"),
+            "probe_bytes_per_clk_per_cu": fill_probe.get("bytes_per_clk_per_cu"),
             "note": "bytes a compute unit pulls into LDS per launch (operand stages of its tiles) / launch time, next to "
                     "what the bare streaming probe reaches at ITS clock (2.4 GHz, nothing else running); at the 1.4 GHz "
                     "the tile loop holds under matrix load (profiles/shader_clock_under_load.md) it moves ~40 B/clk/CU"},
@@ -549,7 +565,7 @@ def main():
         # GEMM alone on the packed operand against the dense GEMMs (the paper's "kernel" speedup)
         "gemm_speedup_vs_dense_linear": round(dense_ms / gemm_ms, 3),
         "gemm_speedup_vs_hipblaslt_dense": round(blas_ms / gemm_ms, 3),
-        "with_lora_r64": None if lora_ms is None else {
+        "with_lora_r64": lora_error if lora_ms is None else {
             "event_ms_per_call": round(lora_ms, 4), "tflops": round(flops / (lora_ms * 1e-3) / 1e12, 1),
             "overhead_vs_sparse_linear": round(lora_ms / call_ms - 1.0, 4),
             "speedup_vs_dense_linear": round(dense_ms / lora_ms, 3),
