@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librtlynx.so")
-SOURCES = ["api.hip", "pack.hip", "gemm.hip", "diag.hip"]
+SOURCES = ["api.hip", "pack.hip", "pack_lora.hip", "gemm.hip", "diag.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed-fp32 instructions are kept out of the generated code on the test machines

@@ -39,7 +39,7 @@ rtl_status device_ready(void** scratch_out = nullptr) {
                 d.state = -1;
             } else {
                 if (rtl::prepare_pack_kernels() != hipSuccess || rtl::prepare_gemm_kernels() != hipSuccess ||
-                    rtl::prepare_diag_kernels() != hipSuccess)
+                    rtl::prepare_pack_lora_kernels() != hipSuccess || rtl::prepare_diag_kernels() != hipSuccess)
                     return RTL_ERR_HIP;
                 void* ptr = nullptr;
                 if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return RTL_ERR_HIP;
@@ -248,11 +248,19 @@ rtl_status rtl_sparse_linear_static(const void* X, const void* W, const void* bi
                             static_cast<hipStream_t>(stream));
 }
 
+// fp32 partial planes of the down-projection: the one-pass sweep (GROUP / NONE) and the separate
+// down-projection kernel (ROW / TENSOR) split the contraction differently
+static size_t lora_partial_bytes(int64_t M, int64_t K, rtl_comp comp) {
+    if (comp == RTL_COMP_NONE || comp == RTL_COMP_GROUP)
+        return (size_t)rtl::pack_down_splits(M, K) * (size_t)M * rtl::kLoraRank * sizeof(float);
+    return rtl::lora_down_partial_bytes(M, K);
+}
+
 // rtl_sparse_lora_linear workspace: [rtl_sparse_linear workspace | T as two bf16 planes [2][M,64] | fp32 partials]
 size_t rtl_sparse_lora_linear_workspace(int64_t M, int64_t N, int64_t K, int64_t R, rtl_comp comp) {
     if (M <= 0 || N <= 0 || K <= 0 || R != rtl::kLoraRank || !comp_ok(comp)) return 0;
     return sparse_ws(M, N, K, comp).total + round_up((size_t)M * rtl::kLoraRank * 4, 256) +
-           round_up(rtl::lora_down_partial_bytes(M, K), 256);
+           round_up(lora_partial_bytes(M, K, comp), 256);
 }
 
 rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, const void* LB,
@@ -270,7 +278,7 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
         return RTL_ERR_ALIGN;
     const SparseWs ws = sparse_ws(M, N, K, comp);
     const size_t t_off = ws.total, p_off = t_off + round_up((size_t)M * rtl::kLoraRank * 4, 256);
-    const size_t need = p_off + round_up(rtl::lora_down_partial_bytes(M, K), 256);
+    const size_t need = p_off + round_up(lora_partial_bytes(M, K, comp), 256);
     if (!workspace || workspace_bytes < need) return RTL_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
     RTL_REQUIRE_DEVICE();
@@ -278,19 +286,28 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
     float* scale = reinterpret_cast<float*>(base + ws.scale);
     uint16_t* T = reinterpret_cast<uint16_t*>(base + t_off);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = rtl::launch_lora_down(static_cast<const uint16_t*>(X), ldx,
-                                         static_cast<const uint16_t*>(LB), ldlb, M, K,
-                                         reinterpret_cast<float*>(base + p_off), s);
-    if (e != hipSuccess) return RTL_ERR_HIP;
-    // the pack sweep also folds the partials into T (two bf16 planes) on its way
-    rtl::LoraReduce fold;
-    fold.partials = reinterpret_cast<const float*>(base + p_off);
-    fold.splits = rtl::lora_down_splits(M, K);
-    fold.T = T;
-    e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr,
-                                  base + ws.vals, base + ws.meta, scale,
-                                  reinterpret_cast<float*>(base + ws.pack), s, fold);
-    if (e != hipSuccess) return RTL_ERR_HIP;
+    hipError_t e;
+    if (comp == RTL_COMP_NONE || comp == RTL_COMP_GROUP) {
+        // one pass over X: the sweep that compresses the activation also forms T = X L_B^T
+        e = rtl::launch_pack_down(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
+                                  static_cast<const uint16_t*>(LB), ldlb, base + ws.vals, base + ws.meta,
+                                  reinterpret_cast<float*>(base + p_off), T, s);
+        if (e != hipSuccess) return RTL_ERR_HIP;
+    } else {
+        // ROW / TENSOR sum along whole rows: separate down-projection, then the pack sweep, which also
+        // folds the partials into T (two bf16 planes) on its way
+        e = rtl::launch_lora_down(static_cast<const uint16_t*>(X), ldx, static_cast<const uint16_t*>(LB), ldlb, M,
+                                  K, reinterpret_cast<float*>(base + p_off), s);
+        if (e != hipSuccess) return RTL_ERR_HIP;
+        rtl::LoraReduce fold;
+        fold.partials = reinterpret_cast<const float*>(base + p_off);
+        fold.splits = rtl::lora_down_splits(M, K);
+        fold.T = T;
+        e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr,
+                                      base + ws.vals, base + ws.meta, scale,
+                                      reinterpret_cast<float*>(base + ws.pack), s, fold);
+        if (e != hipSuccess) return RTL_ERR_HIP;
+    }
     rtl::GemmArgs g{};
     g.A = base + ws.vals;
     g.meta = base + ws.meta;

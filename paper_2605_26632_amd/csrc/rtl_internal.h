@@ -103,6 +103,16 @@ size_t lora_down_partial_bytes(int64_t M, int64_t K);
 hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
                             int64_t K, float* partials, hipStream_t stream);
 
+// One pass over X for the LoRA branch (pack_lora.hip; GROUP and NONE scopes): the sweep writes the k-major
+// compressed operand (as launch_sparsify_pack does) and the fp32 partial planes of T = X L_B^T
+// ([pack_down_splits(M, K)][M][64]), then a second small kernel sums the planes in range order into the
+// two bf16 planes of T ([2][M][64]: hi, lo).
+int pack_down_splits(int64_t M, int64_t K);
+hipError_t prepare_pack_lora_kernels();
+hipError_t launch_pack_down(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp, float eps,
+                            const uint16_t* LB, int64_t ldlb, uint8_t* vals_km, uint8_t* meta_km, float* partials,
+                            uint16_t* T, hipStream_t stream);
+
 // ---- diagnostics (diag.hip) -------------------------------------------------------------------
 // Issue-rate probe: `blocks` workgroups of four waves, each wave issuing 4 * iters matrix
 // instructions (kind 0: dense 32x32x16 bf16, kind 1: structured-sparse 32x32x32 bf16) on register

@@ -370,6 +370,21 @@ def test_packed_linear_scales_and_canonical_operand():
         assert torch.equal(Yp, rtl.sparse_linear(X, W, comp=comp))
 
 
+@pytest.mark.parametrize("comp", [rtl.COMP_NONE, rtl.COMP_GROUP])
+@pytest.mark.parametrize("M,N,K", [(1, 8, 64), (31, 40, 128), (33, 64, 192), (300, 200, 6208), (257, 96, 12288),
+                                   (4608, 64, 3072)])
+def test_block_mapped_sweep_equals_row_mapped_sweep(M, N, K, comp):
+    """rtl_sparse_linear (NONE / GROUP) compresses X with the sweep whose mapping follows the k-major
+    layout; rtl_sparsify_pack + rtl_packed_linear go through the row-mapped sweep (checked bit for bit
+    against the oracle elsewhere) and a re-layout. Same kept values, positions and tile loop, so the
+    outputs must be identical bit for bit. Shapes: a single row, rows short of and just past one 32-row
+    block, one and several 64-k blocks, an odd number of blocks with two per wave (6208 = 97 x 64)."""
+    X = synth.activations("laplace_outlier", M, K, seed=M + K, device=DEV)
+    W = synth.weights(N, K, seed=N + K, device=DEV)
+    vals, meta, _ = rtl.sparsify_pack(X, comp=comp)
+    assert torch.equal(rtl.packed_linear(vals, meta, W), rtl.sparse_linear(X, W, comp=comp))
+
+
 def test_denoising_step_sweep_sampled_blocks():
     """Six of the 60 blocks of the full-step sweep, first and last included (QKV, out-proj, fc1, fc2 at
     M = 4608), fresh seeded tensors per layer: metadata in full, outputs on sampled rows."""
@@ -420,6 +435,35 @@ def test_sparse_lora_linear_zero_factor_equals_sparse_linear():
     LA, LB = synth.lora(W.shape[0], W.shape[1], 64, seed=6, device=DEV)
     Y0 = rtl.sparse_lora_linear(X, W, torch.zeros_like(LA), LB, comp=rtl.COMP_GROUP)
     assert torch.equal(Y0, rtl.sparse_linear(X, W, comp=rtl.COMP_GROUP))
+
+
+@pytest.mark.parametrize("comp", [rtl.COMP_NONE, rtl.COMP_GROUP])
+@pytest.mark.parametrize("shape", ["tiny", "mlp_down", (300, 200, 192), (129, 64, 64), (1000, 128, 1088)])
+def test_one_pass_lora_sweep_writes_the_same_compressed_operand(shape, comp):
+    """GROUP / NONE: the sweep that also forms X L_B^T must leave, bit for bit, the compressed operand
+    (k-major values and metadata, head of the workspace) that the plain sweep of rtl_sparse_linear
+    leaves; rows past M of the padded layout are unspecified and not compared. K = 1088 = 17 blocks
+    leaves the last of its K ranges shorter than the others."""
+    if isinstance(shape, str):
+        X, W = synth.workload(shape, seed=0, device=DEV)
+    else:
+        X = synth.activations("laplace_outlier", shape[0], shape[2], seed=11, device=DEV)
+        W = synth.weights(shape[1], shape[2], seed=12, device=DEV)
+    M, K = X.shape
+    N = W.shape[0]
+    LA, LB = synth.lora(N, K, 64, seed=13, device=DEV)
+    Mpad, KB = (M + 255) // 256 * 256, K // 64
+    vbytes, mbytes = Mpad * KB * 64, Mpad * KB * 8
+    moff = (vbytes + 255) // 256 * 256
+    ws1 = torch.full((rtl.sparse_linear_workspace(M, N, K, comp) + 256,), 0xA5, dtype=torch.uint8, device=DEV)
+    ws2 = torch.full((rtl.sparse_lora_linear_workspace(M, N, K, 64, comp) + 256,), 0x5A, dtype=torch.uint8, device=DEV)
+    rtl.sparse_linear(X, W, comp=comp, ws=ws1)
+    rtl.sparse_lora_linear(X, W, LA, LB, comp=comp, ws=ws2)
+    torch.cuda.synchronize()
+    for ws_a, ws_b, off, rec in ((ws1, ws2, 0, 64), (ws1, ws2, moff, 8)):
+        a = ws_a[off:off + Mpad * KB * rec].view(KB, Mpad, rec)[:, :M]
+        b = ws_b[off:off + Mpad * KB * rec].view(KB, Mpad, rec)[:, :M]
+        assert torch.equal(a, b)
 
 
 @pytest.mark.parametrize("name", ["mlp_down", "fc1"])
