@@ -67,9 +67,10 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
     const uint32_t m2 = max(min(hi01, hi23), hi01 > hi23 ? lo01 : lo23);
     const uint32_t p1 = ~m1 & 3u, p2 = ~m2 & 3u;
     const uint32_t pos0 = min(p1, p2), pos1 = max(p1, p2);
-    const uint64_t x64 = (uint64_t)d0 | ((uint64_t)d1 << 32);
-    uint32_t v0 = (uint32_t)(x64 >> (16u * pos0)) & 0xFFFFu;
-    uint32_t v1 = (uint32_t)(x64 >> (16u * pos1)) & 0xFFFFu;
+    // The kept pair (lower position in the low half) with one byte permute over the 8 bytes of the group:
+    // selector bytes 2 pos0, 2 pos0 + 1, 2 pos1, 2 pos1 + 1 (bytes 0..3 address d0, 4..7 address d1).
+    const uint32_t sel = __umul24(pos0 | (pos1 << 16), 0x0202u) + 0x01000100u;
+    const uint32_t pair = __builtin_amdgcn_perm(d1, d0, sel);
     GroupOut o;
     o.nibble = pos0 | (pos1 << 2);
     o.num = 0.f;
@@ -77,10 +78,11 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
     if constexpr (COMP != RTL_COMP_NONE) {
         const float f0 = bits_to_f32(d0 << 16), f1 = bits_to_f32(d0 & 0xFFFF0000u);
         const float f2 = bits_to_f32(d1 << 16), f3 = bits_to_f32(d1 & 0xFFFF0000u);
-        const float ka = bits_to_f32(v0 << 16), kb = bits_to_f32(v1 << 16);
+        const float ka = bits_to_f32(pair << 16), kb = bits_to_f32(pair & 0xFFFF0000u);
         // squares of bf16 values are exact in fp32; the additions are in the stated order
-        o.num = ((f0 * f0 + f1 * f1) + f2 * f2) + f3 * f3;
-        o.den = ka * ka + kb * kb;
+        // (fused multiply-adds round exactly like a multiply and an add here, see exact_group_scale)
+        o.num = __builtin_fmaf(f3, f3, __builtin_fmaf(f2, f2, __builtin_fmaf(f1, f1, f0 * f0)));
+        o.den = __builtin_fmaf(kb, kb, ka * ka);
         if constexpr (COMP == RTL_COMP_GROUP) {
             // The stored values are bf16_rne(s * k) with s = sqrtf(num / den) in IEEE fp32. The
             // correctly rounded divide and square root cost ~25 instructions, enough to make this
@@ -133,10 +135,10 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
         }
     }
     if constexpr (FP8) {
-        o.packed = e4m3_pair(bits_to_f32(v0 << 16) * inv, bits_to_f32(v1 << 16) * inv);
+        o.packed = e4m3_pair(bits_to_f32(pair << 16) * inv, bits_to_f32(pair & 0xFFFF0000u) * inv);
         return o;
     }
-    o.packed = v0 | (v1 << 16);
+    o.packed = pair;
     return o;
 }
 
