@@ -13,7 +13,8 @@
 // 64-k block, rows contiguous) is written as 64-byte pieces, two neighbouring rows per line.
 // When only the k-major output is wanted and nothing is summed along a row (the rtl_sparse_linear
 // path with NONE / GROUP scope), sparsify_pack_block_kernel runs instead: its mapping follows the
-// output layout (32 rows x 64-k blocks per wave) and every access is a whole line.
+// output layout (32 rows x 64-k blocks per wave) and every access is a whole line. (The FP8 sweep keeps
+// the row mapping: with its heavier per-group arithmetic the block mapping measured the same.)
 #include "rtl_internal.h"
 #include "select.h"
 

@@ -385,6 +385,41 @@ def test_block_mapped_sweep_equals_row_mapped_sweep(M, N, K, comp):
     assert torch.equal(rtl.packed_linear(vals, meta, W), rtl.sparse_linear(X, W, comp=comp))
 
 
+@pytest.mark.parametrize("comp", [rtl.COMP_NONE, rtl.COMP_GROUP])
+@pytest.mark.parametrize("M,K", [(1, 128), (37, 256), (300, 6272), (4608, 3072), (520, 12288)])
+def test_kmajor_operand_is_the_relayout_of_the_canonical_outputs(M, K, comp):
+    """The compressed operand the tile loop streams (head of the workspace after rtl_sparse_linear /
+    rtl_sparse_linear_fp8: values [K/B][Mpad][64 bytes], then metadata [K/B][Mpad][B/8 bytes], B = 64
+    dense k for bf16 and 128 for FP8, Mpad = M rounded up to 256) must hold exactly the bytes of the
+    canonical outputs of rtl_sparsify_pack / rtl_sparsify_pack_fp8, which are checked against the oracle
+    bit for bit: block b of row m = bytes [64 b, 64 b + 64) of the row's values and [B/8 b, B/8 (b + 1)) of
+    its metadata. Rows past M of the padded layout are unspecified."""
+    X = synth.activations("laplace_outlier", M, K, seed=3 * M + K, device=DEV)
+    N = 64
+    W = synth.weights(N, K, seed=5, device=DEV)
+    Mpad = (M + 255) // 256 * 256
+    for fp8 in (False, True):
+        B = 128 if fp8 else 64
+        KB, rec = K // B, B // 8
+        if fp8:
+            xs = (X.float().abs().max() * (2.0 ** 0.5) / 448.0).reshape(1).to(torch.float32)
+            vals, meta, _ = rtl.sparsify_pack_fp8(X, xs, comp=comp)
+            ws = torch.full((rtl.sparse_linear_fp8_workspace(M, N, K, comp) + 256,), 0xA5, dtype=torch.uint8, device=DEV)
+            rtl.sparse_linear_fp8(X, rtl.quantize_fp8(W), xs, comp=comp, ws=ws)
+        else:
+            vals, meta, _ = rtl.sparsify_pack(X, comp=comp)
+            ws = torch.full((rtl.sparse_linear_workspace(M, N, K, comp) + 256,), 0xA5, dtype=torch.uint8, device=DEV)
+            rtl.sparse_linear(X, W, comp=comp, ws=ws)
+        torch.cuda.synchronize()
+        vbytes = vals.contiguous().view(torch.uint8).reshape(M, KB, 64)
+        mbytes = meta.contiguous().view(torch.uint8).reshape(M, KB, rec)
+        moff = (Mpad * KB * 64 + 255) // 256 * 256
+        v_km = ws[:Mpad * KB * 64].view(KB, Mpad, 64)[:, :M]
+        m_km = ws[moff:moff + Mpad * KB * rec].view(KB, Mpad, rec)[:, :M]
+        assert torch.equal(v_km, vbytes.permute(1, 0, 2)), "values, fp8=%s" % fp8
+        assert torch.equal(m_km, mbytes.permute(1, 0, 2)), "metadata, fp8=%s" % fp8
+
+
 def test_denoising_step_sweep_sampled_blocks():
     """Six of the 60 blocks of the full-step sweep, first and last included (QKV, out-proj, fc1, fc2 at
     M = 4608), fresh seeded tensors per layer: metadata in full, outputs on sampled rows."""
