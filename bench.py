@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_kernel_sparse_mlp_down.md
 # (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 KiB after calibration against a plain 1 GiB copy).
 # Summary: profiles/rtl_sparse_linear_kernels_mlp_down.md.
-GEMM_TRAFFIC_BYTES = {"mlp_down": int((184524 * 2.0 + 24576 * 1.0) * 1024)}
+GEMM_TRAFFIC_BYTES = {"mlp_down": int((184459 * 2.0 + 24576 * 1.0) * 1024)}
 
 
 X_KIND = {"gelu": "post-GELU", "laplace": "Laplace rows x log-normal channel scales",
@@ -366,12 +366,12 @@ def main():
 
     # ---- context legs (same shape, same buffers), per-launch HIP-event timing --------------
     n_ev = 100 if not args.only_core else min(args.steps, 100)
-    vals, meta, scale = rtl.sparsify_pack(X, comp=comp)
     # The GEMM kernel alone: rtl_packed_linear takes the canonical metadata and would add the small
-    # re-layout kernel, so the GEMM launch is timed as (whole call) - (its pack kernel), both from
-    # HIP events on the launch stream; the two kernels of a call run back to back on that stream.
+    # re-layout kernel, so the GEMM launch is timed as (whole call) - (its sparsification sweep), both
+    # from HIP events on the launch stream; the two kernels of a call run back to back on that stream.
+    # rtl_diag_pack_sweep launches the sweep exactly as the call does (same kernel, same workspace).
     t_call = event_times(step, n_ev, 10, torch)
-    t_pack = event_times(lambda: rtl.sparsify_pack(X, comp=comp, out=(vals, meta)), n_ev, 10, torch)
+    t_pack = event_times(lambda: rtl.diag_pack_sweep(X, comp=comp, ws=ws), n_ev, 10, torch)
     t_dense = event_times(lambda: rtl.dense_linear(X, W, out=Y, ws=wsd), n_ev, 10, torch)
     t_blas = event_times(lambda: torch.matmul(X, W.t(), out=Y), n_ev, 10, torch)
     # whole Alg. 1 with its rank-64 LoRA residual (context: the paper's linear-layer figures include it)

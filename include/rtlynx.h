@@ -262,6 +262,15 @@ rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, i
 rtl_status rtl_diag_fill_rate(const void* region, size_t region_bytes, int64_t iters, int blocks,
                               uint64_t* clocks, float* sink, void* stream);
 
+/* rtl_diag_pack_sweep - diagnostic: the online sparsification sweep (Alg. 1 "X~ <- TopK(X)",
+ * "S(X) <- s X~", App. A operand format) exactly as rtl_sparse_linear launches it - same kernel, same
+ * compressed operand into the head of the same workspace layout - without the tile loop that follows,
+ * so that the two halves of a call can be timed separately (the benchmark's "Sparse-Cost" share).
+ *   X, M, K, ldx, comp, eps   as for rtl_sparse_linear (K % 64 == 0).
+ *   workspace   device, 256-byte aligned, at least rtl_sparse_linear_workspace(M, 1, K, comp) bytes. */
+rtl_status rtl_diag_pack_sweep(const void* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp, float eps,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* rtl_diag_tile_plan - diagnostic (host arithmetic only, nothing is launched): how the linears cut an
  * [M, N] output into workgroup tiles. plan (HOST pointer, int64[4]) receives {body tile width (256 or
  * 192), rows covered by 256-row body tiles, number of body tiles, number of 256 x 128 tail tiles}.

@@ -21,7 +21,7 @@ SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linea
            "rtl_dense_linear_workspace", "rtl_dense_linear",
            "rtl_quantize_fp8", "rtl_sparsify_pack_fp8_workspace", "rtl_sparsify_pack_fp8",
            "rtl_sparse_linear_fp8_workspace", "rtl_sparse_linear_fp8",
-           "rtl_diag_matrix_rate", "rtl_diag_fill_rate", "rtl_diag_tile_plan", "rtl_init", "rtl_status_str", "rtl_version"]
+           "rtl_diag_matrix_rate", "rtl_diag_fill_rate", "rtl_diag_pack_sweep", "rtl_diag_tile_plan", "rtl_init", "rtl_status_str", "rtl_version"]
 
 _lib = None
 
@@ -78,6 +78,8 @@ def lib():
         L.rtl_diag_matrix_rate.restype = ci
         L.rtl_diag_fill_rate.argtypes = [vp, sz, i64, ci, vp, vp, vp]
         L.rtl_diag_fill_rate.restype = ci
+        L.rtl_diag_pack_sweep.argtypes = [vp, i64, i64, i64, ci, fl, vp, sz, vp]
+        L.rtl_diag_pack_sweep.restype = ci
         L.rtl_diag_tile_plan.argtypes = [i64, i64, ci, C.POINTER(C.c_int64)]
         L.rtl_diag_tile_plan.restype = ci
         L.rtl_init.argtypes = []
@@ -304,6 +306,20 @@ def diag_matrix_rate(kind, operands, iters, blocks=1024):
     st = lib().rtl_diag_matrix_rate(int(kind), _p(operands), int(iters), int(blocks), _p(clocks), _p(sink), _stream())
     _check(st, "rtl_diag_matrix_rate")
     return clocks, float(blocks) * 4 * 4 * iters * 2 * 32 * 32 * 16
+
+
+def diag_pack_sweep(X, comp=COMP_GROUP, eps=1e-8, ws=None):
+    """rtl_diag_pack_sweep: the sparsification sweep as rtl_sparse_linear launches it, alone (for timing);
+    the compressed operand lands in the head of `ws` (an rtl_sparse_linear workspace)."""
+    _need_cuda(X)
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    L = lib()
+    if ws is None:
+        ws = _ws(L.rtl_sparse_linear_workspace(M, 1, K, comp), X.device)
+    _check(L.rtl_diag_pack_sweep(_p(X), M, K, X.stride(0), comp, eps, _p(ws), ws.numel(), _stream()),
+           "rtl_diag_pack_sweep")
+    return ws
 
 
 def diag_tile_plan(M, N, dense=False):

@@ -433,6 +433,26 @@ rtl_status rtl_diag_fill_rate(const void* region, size_t region_bytes, int64_t i
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
 
+rtl_status rtl_diag_pack_sweep(const void* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp, float eps,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    if (M < 0 || K <= 0 || K % 64 != 0 || ldx < K || M > ((int64_t)1 << 30) || K > ((int64_t)1 << 30) ||
+        ldx > ((int64_t)1 << 22))
+        return RTL_ERR_SHAPE;
+    if (M == 0) return RTL_OK;
+    if (!X) return RTL_ERR_NULL;
+    if (ldx % 8 != 0 || !aligned(X, 16)) return RTL_ERR_ALIGN;
+    const SparseWs ws = sparse_ws(M, 1, K, comp);
+    if (!workspace || workspace_bytes < ws.total) return RTL_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    hipError_t e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr,
+                                             base + ws.vals, base + ws.meta, reinterpret_cast<float*>(base + ws.scale),
+                                             reinterpret_cast<float*>(base + ws.pack), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
 rtl_status rtl_diag_tile_plan(int64_t M, int64_t N, int dense, int64_t* plan) {
     if (M <= 0 || N <= 0 || M > ((int64_t)1 << 30) || N > ((int64_t)1 << 30)) return RTL_ERR_SHAPE;
     if (!plan) return RTL_ERR_NULL;

@@ -420,6 +420,22 @@ def test_kmajor_operand_is_the_relayout_of_the_canonical_outputs(M, K, comp):
         assert torch.equal(m_km, mbytes.permute(1, 0, 2)), "metadata, fp8=%s" % fp8
 
 
+@pytest.mark.parametrize("comp", COMPS)
+def test_diag_pack_sweep_is_the_first_half_of_sparse_linear(comp):
+    """rtl_diag_pack_sweep (what bench.py times as the sparsification share of a call) must leave the
+    workspace exactly as the sweep inside rtl_sparse_linear leaves it: compressed operand, and the
+    ROW / TENSOR factors behind it."""
+    X, W = synth.workload("tiny", seed=8, device=DEV)
+    M, K = X.shape
+    n = rtl.sparse_linear_workspace(M, W.shape[0], K, comp)
+    ws1 = torch.full((n + 256,), 0x11, dtype=torch.uint8, device=DEV)
+    ws2 = torch.full((n + 256,), 0x11, dtype=torch.uint8, device=DEV)
+    rtl.sparse_linear(X, W, comp=comp, ws=ws1)
+    rtl.diag_pack_sweep(X, comp=comp, ws=ws2)
+    torch.cuda.synchronize()
+    assert torch.equal(ws1, ws2)
+
+
 def test_denoising_step_sweep_sampled_blocks():
     """Six of the 60 blocks of the full-step sweep, first and last included (QKV, out-proj, fc1, fc2 at
     M = 4608), fresh seeded tensors per layer: metadata in full, outputs on sampled rows."""
