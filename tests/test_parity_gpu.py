@@ -489,7 +489,8 @@ def test_sparse_lora_linear_zero_factor_equals_sparse_linear():
 
 
 @pytest.mark.parametrize("comp", [rtl.COMP_NONE, rtl.COMP_GROUP])
-@pytest.mark.parametrize("shape", ["tiny", "mlp_down", (300, 200, 192), (129, 64, 64), (1000, 128, 1088)])
+@pytest.mark.parametrize("shape", ["tiny", "mlp_down", "hr_out_proj", "hr_mlp_down", (300, 200, 192), (129, 64, 64),
+                                   (1000, 128, 1088)])
 def test_one_pass_lora_sweep_writes_the_same_compressed_operand(shape, comp):
     """GROUP / NONE: the sweep that also forms X L_B^T must leave, bit for bit, the compressed operand
     (k-major values and metadata, head of the workspace) that the plain sweep of rtl_sparse_linear
@@ -517,7 +518,7 @@ def test_one_pass_lora_sweep_writes_the_same_compressed_operand(shape, comp):
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("name", ["mlp_down", "fc1"])
+@pytest.mark.parametrize("name", ["mlp_down", "fc1", "hr_out_proj", "ar32_qkv"])
 def test_sparse_lora_linear_full_size_sampled_rows(name):
     X, W = synth.workload(name, seed=0, device=DEV)
     M, K = X.shape
