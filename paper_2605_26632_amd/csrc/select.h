@@ -117,8 +117,12 @@ __device__ __forceinline__ GroupOut select_group(uint32_t d0, uint32_t d1, float
                     s = exact_group_scale(f0, f1, f2, f3, ka, kb, eps);
                     t0 = (s * ka) * inv;
                     t1 = (s * kb) * inv;
+                    o.packed = e4m3_pair(t0, t1);
+                } else if (fmaxf(fabsf(t0), fabsf(t1)) <= 448.0f) {
+                    o.packed = c_below & 0xFFFFu;      // inside the format's range the raw conversion is the code
+                } else {
+                    o.packed = e4m3_pair(t0, t1);      // saturating values: the raw conversion returns NaN codes
                 }
-                o.packed = e4m3_pair(t0, t1);
                 return o;
             }
             if (near | odd_range) {
