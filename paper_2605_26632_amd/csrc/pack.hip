@@ -165,11 +165,12 @@ constexpr int kBlockUnroll = 2;     // 64-k blocks in flight per wave
 template <int COMP>
 __global__ __launch_bounds__(kBlockWaves * 64) void sparsify_pack_block_kernel(
     const uint16_t* __restrict__ X, int64_t M, int KB, int64_t ldx, float eps, uint8_t* __restrict__ vals_km,
-    uint8_t* __restrict__ meta_km, int64_t Mpad, int per) {
+    uint8_t* __restrict__ meta_km, int64_t Mpad, int per, unsigned row_blocks) {
     const int lane = threadIdx.x & 63, r8 = lane >> 3, c = lane & 7;
     const int wave = threadIdx.x >> 6;
-    const int64_t m0 = (int64_t)blockIdx.x * 32;
-    const int b0 = ((int)blockIdx.y * kBlockWaves + wave) * per;       // first block of this wave's run
+    // workgroup id = run group * row_blocks + row block: neighbours take neighbouring rows of one K range
+    const int64_t m0 = (int64_t)(blockIdx.x % row_blocks) * 32;
+    const int b0 = ((int)(blockIdx.x / row_blocks) * kBlockWaves + wave) * per;   // first block of this wave's run
     const int b1 = min(KB, b0 + per);
     const uint16_t* xr[4];
 #pragma unroll
@@ -310,14 +311,17 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
             const int KB = (int)(K / 64);
             const int per = KB >= 96 ? kBlockUnroll : 1;
             const int runs = (KB + per - 1) / per;                     // waves per 32 rows
-            const dim3 grid((unsigned)((M + 31) / 32), (unsigned)((runs + kBlockWaves - 1) / kBlockWaves));
-            if (comp == RTL_COMP_GROUP)
-                hipLaunchKernelGGL((sparsify_pack_block_kernel<RTL_COMP_GROUP>), grid, dim3(kBlockWaves * 64), 0, stream,
-                                   X, M, KB, ldx, eps, vals_km, meta_km, Mpad, per);
-            else
-                hipLaunchKernelGGL((sparsify_pack_block_kernel<RTL_COMP_NONE>), grid, dim3(kBlockWaves * 64), 0, stream,
-                                   X, M, KB, ldx, eps, vals_km, meta_km, Mpad, per);
-            return hipGetLastError();
+            const int64_t row_blocks = (M + 31) / 32, groups = (runs + kBlockWaves - 1) / kBlockWaves;
+            if (row_blocks * groups < ((int64_t)1 << 31)) {            // (else: far beyond memory; the row mapping serves)
+                const dim3 grid((unsigned)(row_blocks * groups));
+                if (comp == RTL_COMP_GROUP)
+                    hipLaunchKernelGGL((sparsify_pack_block_kernel<RTL_COMP_GROUP>), grid, dim3(kBlockWaves * 64), 0,
+                                       stream, X, M, KB, ldx, eps, vals_km, meta_km, Mpad, per, (unsigned)row_blocks);
+                else
+                    hipLaunchKernelGGL((sparsify_pack_block_kernel<RTL_COMP_NONE>), grid, dim3(kBlockWaves * 64), 0,
+                                       stream, X, M, KB, ldx, eps, vals_km, meta_km, Mpad, per, (unsigned)row_blocks);
+                return hipGetLastError();
+            }
         }
     }
     // Waves per row: two once each still has a full unrolled trip of work (measured: 34 -> 31 us at
