@@ -94,9 +94,10 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream);
 // by body tiles, number of body tiles, number of 256 x 128 tail tiles}. Host arithmetic only.
 void tile_plan(int64_t M, int64_t N, bool dense, int64_t out[4]);
 
-// LoRA down-projection, first half: split-K partial products of T = X L_B^T into `partials`
-// ([splits][M][64] fp32, splits = lora_down_splits(M, K)). The ordered reduction to the bf16 hi/lo
-// planes rides on the pack sweep that follows (LoraReduce above).
+// LoRA down-projection as a sweep of its own (ROW / TENSOR scopes; NONE / GROUP use launch_pack_down
+// below): split-K partial products of T = X L_B^T into `partials` ([splits][M][64] fp32, splits =
+// lora_down_splits(M, K)). The ordered reduction to the bf16 hi/lo planes rides on the pack sweep that
+// follows (LoraReduce above).
 constexpr int kLoraRank = 64;
 int lora_down_splits(int64_t M, int64_t K);
 size_t lora_down_partial_bytes(int64_t M, int64_t K);
