@@ -436,6 +436,30 @@ def test_diag_pack_sweep_is_the_first_half_of_sparse_linear(comp):
     assert torch.equal(ws1, ws2)
 
 
+@pytest.mark.parametrize("comp", COMPS)
+def test_linears_on_strided_views(comp):
+    """X, W and Y as column windows of wider buffers (ldx > K, ldw > K, ldy > N; bases 16-byte aligned but
+    not line aligned): rtl_sparse_linear and rtl_sparse_lora_linear must equal the same calls on contiguous
+    copies bit for bit, and leave the rest of the Y buffer alone."""
+    M, N, K = 333, 200, 448
+    bigX = synth.activations("laplace_outlier", M, K + 192, seed=21, device=DEV)
+    bigW = synth.weights(N, K + 128, seed=22, device=DEV)
+    X, W = bigX[:, 8:8 + K], bigW[:, 8:8 + K]
+    LA, LB = synth.lora(N, K, 64, seed=23, device=DEV, std_a=0.3, std_b=0.3)
+    b = synth.bias(N, seed=24, device=DEV)
+    for lora in (False, True):
+        bigY = torch.full((M, N + 40), 7.0, dtype=torch.bfloat16, device=DEV)
+        Y = bigY[:, 16:16 + N]
+        if lora:
+            rtl.sparse_lora_linear(X, W, LA, LB, bias=b, comp=comp, out=Y)
+            ref = rtl.sparse_lora_linear(X.contiguous(), W.contiguous(), LA, LB, bias=b, comp=comp)
+        else:
+            rtl.sparse_linear(X, W, bias=b, comp=comp, out=Y)
+            ref = rtl.sparse_linear(X.contiguous(), W.contiguous(), bias=b, comp=comp)
+        assert torch.equal(Y, ref)
+        assert (bigY[:, :16] == 7.0).all() and (bigY[:, 16 + N:] == 7.0).all()
+
+
 def test_denoising_step_sweep_sampled_blocks():
     """Six of the 60 blocks of the full-step sweep, first and last included (QKV, out-proj, fc1, fc2 at
     M = 4608), fresh seeded tensors per layer: metadata in full, outputs on sampled rows."""
