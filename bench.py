@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_kernel_sparse_mlp_down.md
 # (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 KiB after calibration against a plain 1 GiB copy).
 # Summary: profiles/rtl_sparse_linear_kernels_mlp_down.md.
-GEMM_TRAFFIC_BYTES = {"mlp_down": int((184459 * 2.0 + 24576 * 1.0) * 1024)}
+GEMM_TRAFFIC_BYTES = {"mlp_down": int((184458 * 2.0 + 24576 * 1.0) * 1024)}
 
 
 X_KIND = {"gelu": "post-GELU", "laplace": "Laplace rows x log-normal channel scales",
