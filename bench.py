@@ -268,8 +268,23 @@ def run_sweep(args, torch, rtl, synth, dev, comp):
             else:
                 rtl.sparse_linear_fp8(x, q, sc, comp=comp, out=outs[kind], ws=ws)
 
+    # the whole Alg. 1 per layer: rank-64 LoRA residual on every sparse layer (factors per layer)
+    lora = [synth.lora(w.shape[0], w.shape[1], 64, seed=synth.layer_seed(i // len(synth.SWEEP_LAYERS), kind) + 900,
+                       device=dev) for i, (kind, _, w) in enumerate(layers)]
+    wsl_bytes = max(rtl.sparse_lora_linear_workspace(M, synth.WORKLOADS[k]["N"], synth.WORKLOADS[k]["K"], 64, comp)
+                    for k in synth.SWEEP_LAYERS)
+    wsl = torch.empty(wsl_bytes + 256, dtype=torch.uint8, device=dev)
+
+    def lora_pass():
+        for (kind, x, w), (la, lb) in zip(layers, lora):
+            if kind in skip:
+                rtl.dense_linear(x, w, out=outs[kind], ws=ws)
+            else:
+                rtl.sparse_lora_linear(x, w, la, lb, comp=comp, out=outs[kind], ws=wsl)
+
     steps, warmup = min(args.steps, 10), min(args.warmup, 2)
     ms_sparse = timed(sparse_pass, steps, warmup)
+    ms_lora = timed(lora_pass, steps, warmup)
     ms_dense = timed(dense_pass, steps, warmup)
     ms_blas = timed(blas_pass, steps, warmup)
     ms_fp8 = timed(fp8_pass, steps, warmup)
@@ -285,7 +300,10 @@ def run_sweep(args, torch, rtl, synth, dev, comp):
         "speedup_vs_dense_linear": round(ms_dense / ms_sparse, 3),
         "speedup_vs_hipblaslt_dense": round(ms_blas / ms_sparse, 3),
         "speedup_vs_best_dense": round(min(ms_dense, ms_blas) / ms_sparse, 3),
-        "clocks_used": "host wall clock over whole passes for all four legs",
+        "clocks_used": "host wall clock over whole passes for all five legs",
+        "with_lora_r64": {"ms_per_step": round(ms_lora, 3), "tflops": round(flops / (ms_lora * 1e-3) / 1e12, 1),
+                          "overhead_vs_sparse_linear": round(ms_lora / ms_sparse - 1.0, 4),
+                          "speedup_vs_best_dense": round(min(ms_dense, ms_blas) / ms_lora, 3)},
         "with_fp8_e4m3": {"ms_per_step": round(ms_fp8, 3), "tflops": round(flops / (ms_fp8 * 1e-3) / 1e12, 1)},
         "roofline": None, "cpu_baseline": None}))
 
