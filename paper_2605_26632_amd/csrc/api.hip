@@ -180,7 +180,6 @@ rtl_status rtl_packed_linear(const void* vals, const void* meta, const float* ro
     g.row_scale = row_scale;
     g.tensor_scale = tensor_scale;
     g.Y = static_cast<uint16_t*>(Y);
-    g.partials = reinterpret_cast<float*>(km + round_up(rtl::kmajor_bytes(M, K), 256));
     g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
@@ -210,7 +209,6 @@ static rtl_status sparse_linear_on(uint8_t* base, const SparseWs& ws, const void
     g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
     g.tensor_scale = comp == RTL_COMP_TENSOR ? scale : nullptr;
     g.Y = static_cast<uint16_t*>(Y);
-    g.partials = reinterpret_cast<float*>(base + ws.gemm);
     g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, s);
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
@@ -248,19 +246,12 @@ rtl_status rtl_sparse_linear_static(const void* X, const void* W, const void* bi
                             static_cast<hipStream_t>(stream));
 }
 
-// fp32 partial planes of the down-projection: the one-pass sweep (GROUP / NONE) and the separate
-// down-projection kernel (ROW / TENSOR) split the contraction differently
-static size_t lora_partial_bytes(int64_t M, int64_t K, rtl_comp comp) {
-    if (comp == RTL_COMP_NONE || comp == RTL_COMP_GROUP)
-        return (size_t)rtl::pack_down_splits(M, K) * (size_t)M * rtl::kLoraRank * sizeof(float);
-    return rtl::lora_down_partial_bytes(M, K);
-}
-
-// rtl_sparse_lora_linear workspace: [rtl_sparse_linear workspace | T as two bf16 planes [2][M,64] | fp32 partials]
+// rtl_sparse_lora_linear workspace: [rtl_sparse_linear workspace | T as two bf16 planes [2][M,64] |
+// per-K-range partial planes and row sums of the one-pass sweep]
 size_t rtl_sparse_lora_linear_workspace(int64_t M, int64_t N, int64_t K, int64_t R, rtl_comp comp) {
     if (M <= 0 || N <= 0 || K <= 0 || R != rtl::kLoraRank || !comp_ok(comp)) return 0;
     return sparse_ws(M, N, K, comp).total + round_up((size_t)M * rtl::kLoraRank * 4, 256) +
-           round_up(lora_partial_bytes(M, K, comp), 256);
+           round_up(rtl::pack_down_scratch_bytes(M, K), 256);
 }
 
 rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, const void* LB,
@@ -278,7 +269,7 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
         return RTL_ERR_ALIGN;
     const SparseWs ws = sparse_ws(M, N, K, comp);
     const size_t t_off = ws.total, p_off = t_off + round_up((size_t)M * rtl::kLoraRank * 4, 256);
-    const size_t need = p_off + round_up(lora_partial_bytes(M, K, comp), 256);
+    const size_t need = p_off + round_up(rtl::pack_down_scratch_bytes(M, K), 256);
     if (!workspace || workspace_bytes < need) return RTL_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
     RTL_REQUIRE_DEVICE();
@@ -286,28 +277,12 @@ rtl_status rtl_sparse_lora_linear(const void* X, const void* W, const void* LA, 
     float* scale = reinterpret_cast<float*>(base + ws.scale);
     uint16_t* T = reinterpret_cast<uint16_t*>(base + t_off);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e;
-    if (comp == RTL_COMP_NONE || comp == RTL_COMP_GROUP) {
-        // one pass over X: the sweep that compresses the activation also forms T = X L_B^T
-        e = rtl::launch_pack_down(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
-                                  static_cast<const uint16_t*>(LB), ldlb, base + ws.vals, base + ws.meta,
-                                  reinterpret_cast<float*>(base + p_off), T, s);
-        if (e != hipSuccess) return RTL_ERR_HIP;
-    } else {
-        // ROW / TENSOR sum along whole rows: separate down-projection, then the pack sweep, which also
-        // folds the partials into T (two bf16 planes) on its way
-        e = rtl::launch_lora_down(static_cast<const uint16_t*>(X), ldx, static_cast<const uint16_t*>(LB), ldlb, M,
-                                  K, reinterpret_cast<float*>(base + p_off), s);
-        if (e != hipSuccess) return RTL_ERR_HIP;
-        rtl::LoraReduce fold;
-        fold.partials = reinterpret_cast<const float*>(base + p_off);
-        fold.splits = rtl::lora_down_splits(M, K);
-        fold.T = T;
-        e = rtl::launch_sparsify_pack(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps, nullptr, nullptr,
-                                      base + ws.vals, base + ws.meta, scale,
-                                      reinterpret_cast<float*>(base + ws.pack), s, fold);
-        if (e != hipSuccess) return RTL_ERR_HIP;
-    }
+    // one pass over X: the sweep that compresses the activation also forms T = X L_B^T
+    hipError_t e = rtl::launch_pack_down(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
+                                         static_cast<const uint16_t*>(LB), ldlb, base + ws.vals, base + ws.meta,
+                                         reinterpret_cast<float*>(base + p_off), T, scale,
+                                         reinterpret_cast<float*>(base + ws.pack), s);
+    if (e != hipSuccess) return RTL_ERR_HIP;
     rtl::GemmArgs g{};
     g.A = base + ws.vals;
     g.meta = base + ws.meta;
@@ -401,7 +376,6 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
     g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
     g.tensor_scale = comp == RTL_COMP_TENSOR ? fused : x_scale;   // dequantisation rides on the epilogue
     g.Y = static_cast<uint16_t*>(Y);
-    g.partials = reinterpret_cast<float*>(base + ws.gemm);
     g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
     e = rtl::launch_gemm(true, g, s);
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
@@ -480,7 +454,6 @@ rtl_status rtl_dense_linear(const void* X, const void* W, const void* bias, void
     g.W = W;
     g.bias = static_cast<const uint16_t*>(bias);
     g.Y = static_cast<uint16_t*>(Y);
-    g.partials = static_cast<float*>(workspace);
     g.M = M; g.N = N; g.K = K; g.lda = ldx; g.ldw = ldw; g.ldy = ldy;
     hipError_t e = rtl::launch_gemm(false, g, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;

@@ -160,14 +160,13 @@ __device__ __forceinline__ void tile_walk(int t, int tiles_m, int tiles_n, int& 
 }
 
 // MODE 0: plain linear. MODE 1 (sparse only): LoRA tail, the accumulators also receive T L_A^T before
-// the epilogue. MODE 2: split contraction, grid.y K ranges, fp32 partial tiles instead of Y.
-// `tile`: index of this workgroup's output tile in the walk of the (M / BM) x (N / BN) tile grid;
-// `pid_y`: K range of a split contraction (MODE 2).
+// the epilogue.
+// `tile`: index of this workgroup's output tile in the walk of the (M / BM) x (N / BN) tile grid.
 template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
           bool D64 = false>
-__device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile, const int pid_y) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile) {
     static_assert(!D64 || (!SPARSE && MODE != 1), "64-k stages: dense kernels only");
-    static_assert(MODE == 0 || (MODE == 1 && SPARSE) || (MODE == 2 && !SPARSE), "mode/operand combination");
+    static_assert(MODE == 0 || (MODE == 1 && SPARSE), "mode/operand combination");
     static_assert(!FP8 || (SPARSE && MODE == 0), "FP8 operands: plain sparse kernel only");
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -204,21 +203,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile, cons
     int pm, pn;
     tile_walk(tile, tiles_m, tiles_n, pm, pn);
     const int64_t m0 = (int64_t)pm * BM, n0 = (int64_t)pn * BN;
-    int KT = (int)(a.K / KSTAGE);
-    int kt_first = 0;                                  // first stage of this workgroup's K range
-    if constexpr (MODE == 2) {
-        const int per = (KT + a.splits - 1) / a.splits;
-        kt_first = pid_y * per;
-        KT = max(0, min(per, KT - kt_first));
-        if (KT <= 0) {   // cannot happen for the range counts the launcher picks; stay defined anyway
-            float* out = a.partials + (int64_t)pid_y * a.M * a.N;
-            for (int e = tid; e < BM * BN; e += NW * 64) {
-                const int64_t row = m0 + e / BN, col = n0 + e % BN;
-                if (row < a.M && col < a.N) out[row * a.N + col] = 0.f;
-            }
-            return;
-        }
-    }
+    const int KT = (int)(a.K / KSTAGE);
 
     // ---- global -> LDS: every lane owns fixed chunks; rows past the edge are clamped to the last
     //      valid row (their products only reach outputs that are never stored) -----------------
@@ -228,9 +213,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile, cons
     const int64_t rows_pad = a.rows_pad;    // rows per k block of the k-major operand (whole activation)
     const int64_t a_stride = SPARSE ? rows_pad * 64 : (int64_t)(A_ELEMS * ESZ);   // bytes between stages
     const uint8_t* base_a = SPARSE
-        ? static_cast<const uint8_t*>(a.A) + m0 * 64 + (int64_t)kt_first * a_stride
-        : static_cast<const uint8_t*>(a.A) + (m0 * a.lda + (int64_t)kt_first * A_ELEMS) * ESZ;
-    const uint8_t* base_b = static_cast<const uint8_t*>(a.W) + (n0 * a.ldw + (int64_t)kt_first * KSTAGE) * ESZ;
+        ? static_cast<const uint8_t*>(a.A) + m0 * 64
+        : static_cast<const uint8_t*>(a.A) + m0 * a.lda * ESZ;
+    const uint8_t* base_b = static_cast<const uint8_t*>(a.W) + n0 * a.ldw * ESZ;
     const int64_t rows_a = a.M - m0, rows_b = a.N - n0;     // valid rows from the tile's first row
     uint32_t oa[A_PER_W];
 #pragma unroll
@@ -539,24 +524,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile, cons
 
     const float ts = a.tensor_scale ? a.tensor_scale[0] : 1.0f;
 
-    if constexpr (MODE == 2) {
-        // ---- split contraction: fp32 partial tile of this K range, no epilogue arithmetic ----
-        float* out = a.partials + (int64_t)pid_y * a.M * a.N;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = n0 + wn * WTN + j * 32 + li;
-            if (col >= a.N) continue;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t row = m0 + wm * WTM + i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
-                    if (row < a.M) out[row * a.N + col] = acc[i][j][r];
-                }
-        }
-        return;
-    }
-
     if constexpr (MODE == 1) {
         // ---- LoRA tail (Alg. 1: Y <- Y_s + Y_r, accumulated on chip) --------------------------
         // The ROW / TENSOR factors belong to the sparse product only, so they are applied to the
@@ -670,24 +637,40 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile, cons
                     for (int r = 0; r < 16; r += 2)
                         put2(acc[i][j][r], acc[i][j][r + 1], i * 32 + 8 * (r / 4) + 4 * kb + (r % 4), j * 32 + li);
         } else {
+            // the factors of the lane's 16 rows per row block are fetched once, not once per column block,
+            // four consecutive rows per load, all loads in flight together
+            float bv[TN];
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int64_t col = min(n0 + wn * WTN + j * 32 + li, a.N - 1);
-                const float bv = a.bias ? __uint_as_float((uint32_t)a.bias[col] << 16) : 0.f;
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 2) {
-                        const int rl = i * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
-                        float f0 = 1.0f, f1 = 1.0f;
-                        if (scaled) {
-                            const int64_t row = min(m0 + wm * WTM + rl, a.M - 1);
-                            f0 = (a.row_scale ? a.row_scale[row] : 1.0f) * ts;
-                            f1 = (a.row_scale ? a.row_scale[min(row + 1, a.M - 1)] : 1.0f) * ts;
-                        }
-                        put2(acc[i][j][r] * f0 + bv, acc[i][j][r + 1] * f1 + bv, rl, j * 32 + li);
-                    }
+                bv[j] = a.bias ? __uint_as_float((uint32_t)a.bias[col] << 16) : 0.f;
             }
+            float f[TM][16];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {       // registers 4 q .. 4 q + 3 are four consecutive rows
+                    const int64_t row = m0 + wm * WTM + i * 32 + 8 * q + 4 * kb;
+                    if (!scaled || !a.row_scale) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) f[i][4 * q + e] = 1.0f;
+                    } else if (row + 3 < a.M && (reinterpret_cast<uintptr_t>(a.row_scale + row) & 15) == 0) {
+                        const float4 v = *reinterpret_cast<const float4*>(a.row_scale + row);
+                        f[i][4 * q] = v.x; f[i][4 * q + 1] = v.y; f[i][4 * q + 2] = v.z; f[i][4 * q + 3] = v.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) f[i][4 * q + e] = a.row_scale[min(row + e, a.M - 1)];
+                    }
+                }
+            const float tsf = scaled ? ts : 1.0f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2)
+                        put2(acc[i][j][r] * (f[i][r] * tsf) + bv[j], acc[i][j][r + 1] * (f[i][r + 1] * tsf) + bv[j],
+                             i * 32 + 8 * (r / 4) + 4 * kb + (r % 4), j * 32 + li);
         }
         // same wave reads back what it wrote: LDS operations of a wave complete in order
         constexpr int CPR = WTN / 8;               // 16-byte chunks per tile row
@@ -730,15 +713,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile, cons
     }
 }
 
-// One tile shape per launch (used for the split contraction of the LoRA down-projection).
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
-          bool D64 = false>
-__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
-    const int tiles = (int)(((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN));
-    gemm_tile<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>(
-        a, xcd_share_start(tiles, (int)blockIdx.x % 8) + (int)blockIdx.x / 8, (int)blockIdx.y);
-}
-
 // Two tile shapes in one launch (the "block-parallel" balancing of the method section's kernel
 // paragraph, done with tile shapes instead of split contractions): rows [0, m_split) of the output
 // are cut into 256 x BN body tiles, rows [m_split, M) into 256 x 128 tail tiles. Uniform tiles
@@ -756,7 +730,7 @@ __global__ __launch_bounds__(512) void gemm_mixed_kernel(const GemmArgs a) {
     if (local < nb_x) {
         GemmArgs b = a;
         if (nt > 0) b.M = a.m_split;
-        gemm_tile<SPARSE, 256, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>(b, xcd_share_start(nb, xcd) + local, 0);
+        gemm_tile<SPARSE, 256, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>(b, xcd_share_start(nb, xcd) + local);
     } else {
         // the tail region as a problem of its own: same operands, shifted by m_split rows
         constexpr int ESZ = FP8 ? 1 : 2;
@@ -768,7 +742,7 @@ __global__ __launch_bounds__(512) void gemm_mixed_kernel(const GemmArgs a) {
         if (a.row_scale) t.row_scale = a.row_scale + a.m_split;
         if constexpr (MODE == 1) t.T = a.T + a.m_split * kLoraRank;
         const int idx = xcd_share_start(nb + nt, xcd) - xcd_share_start(nb, xcd) + (local - nb_x);
-        gemm_tile<SPARSE, 256, kTailBN, 2, 4, STAGES, MODE, FP8, D64>(t, idx, 0);
+        gemm_tile<SPARSE, 256, kTailBN, 2, 4, STAGES, MODE, FP8, D64>(t, idx);
     }
 }
 
@@ -776,26 +750,6 @@ __global__ __launch_bounds__(512) void gemm_mixed_kernel(const GemmArgs a) {
 // per kernel by the prepare functions (called for every configuration from prepare_gemm_kernels, i.e.
 // from rtl_init or from the first entry-point call on a device), never from a launch, so that launches
 // consist of the kernel node only and can be recorded into a HIP graph.
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
-          bool D64 = false>
-hipError_t prepare_cfg() {
-    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
-    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               L::kTotal);
-}
-
-template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false,
-          bool D64 = false>
-hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
-    using L = Smem<SPARSE, BM, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
-    auto kern = gemm_kernel<SPARSE, BM, BN, WAVES_M, WAVES_N, STAGES, MODE, FP8, D64>;
-    const int64_t tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    const dim3 grid((unsigned)tiles, MODE == 2 ? (unsigned)a.splits : 1u);
-    hipLaunchKernelGGL(kern, grid, dim3(WAVES_M * WAVES_N * 64), L::kTotal, stream, a);
-    return hipGetLastError();
-}
-
 template <bool SPARSE, int BN, int WAVES_M, int WAVES_N, int STAGES, int MODE = 0, bool FP8 = false, bool D64 = false>
 struct Mixed {
     using LB = Smem<SPARSE, 256, BN, STAGES, WAVES_M, WAVES_N, FP8, D64>;
@@ -901,7 +855,7 @@ void tile_plan(int64_t M, int64_t N, bool dense, int64_t out[4]) {
     out[3] = p.tail_tiles;
 }
 
-// Every configuration launch_gemm and launch_lora_down can pick.
+// Every configuration launch_gemm can pick.
 hipError_t prepare_gemm_kernels() {
     hipError_t e = hipSuccess;
     auto run = [&](hipError_t r) { if (e == hipSuccess) e = r; };
@@ -913,7 +867,6 @@ hipError_t prepare_gemm_kernels() {
     run(Mixed<true, 256, 2, 4, 3>::prepare());
     run(Mixed<false, 192, 4, 2, 2, 0, false, true>::prepare());
     run(Mixed<false, 256, 2, 4, 2, 0, false, true>::prepare());
-    run(prepare_cfg<false, 128, 64, 4, 1, 4, 2, false, true>());
     return e;
 }
 
@@ -941,35 +894,6 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a_in, hipStream_t stream) {
     // dense: stages of 64 k (whole-line requests on the row-major operands), ring of two
     if (plan.use_192) return Mixed<false, 192, 4, 2, 2, 0, false, true>::launch(a, stream);
     return Mixed<false, 256, 2, 4, 2, 0, false, true>::launch(a, stream);
-}
-
-// ---- LoRA down-projection: a skinny product (N = 64) bound by reading X once. 128-row tiles times
-// enough K ranges to occupy every CU; the ranges are summed in a fixed order by a second kernel.
-static int lora_ranges(int64_t M, int64_t K, int* per_out) {
-    const int64_t tiles = (M + 127) / 128;
-    const int KT = (int)(K / 64);
-    // Enough ranges to occupy every CU, and at least 8: workgroups that walk different parts of K
-    // touch different memory channels at any moment (rows are a large power-of-two-ish stride apart),
-    // which matters once M alone would fill the chip (measured at M = 16896, K = 12288: 163 us with
-    // 2 ranges, 114 us with 8; 4 to 12 ranges are equivalent, more cost partial-sum traffic).
-    int want = (int)((256 + tiles - 1) / tiles);
-    want = want < 8 ? 8 : (want > 16 ? 16 : want);
-    if (want > KT) want = KT;
-    const int per = (KT + want - 1) / want;
-    if (per_out) *per_out = per;
-    return (KT + per - 1) / per;           // every range holds at least one stage
-}
-int lora_down_splits(int64_t M, int64_t K) { return lora_ranges(M, K, nullptr); }
-size_t lora_down_partial_bytes(int64_t M, int64_t K) {
-    return (size_t)lora_down_splits(M, K) * (size_t)M * kLoraRank * sizeof(float);
-}
-hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
-                            int64_t K, float* partials, hipStream_t stream) {
-    GemmArgs g{};
-    g.A = X; g.W = LB; g.partials = partials;
-    g.M = M; g.N = kLoraRank; g.K = K; g.lda = ldx; g.ldw = ldlb; g.ldy = kLoraRank;
-    g.splits = lora_down_splits(M, K);
-    return launch_cfg<false, 128, 64, 4, 1, 4, 2, false, true>(g, stream);
 }
 
 }  // namespace rtl

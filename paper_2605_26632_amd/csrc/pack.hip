@@ -41,33 +41,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sparsify_pack_kernel(
     const uint16_t* __restrict__ X, int64_t M, int K, int64_t ldx, float eps,
     void* __restrict__ vals, uint8_t* __restrict__ meta, uint8_t* __restrict__ vals_km,
     uint8_t* __restrict__ meta_km, int64_t Mpad, float* __restrict__ scale,
-    float* __restrict__ rowsums, const float* __restrict__ x_scale, int parts, LoraReduce lora) {
+    float* __restrict__ rowsums, const float* __restrict__ x_scale, int parts) {
     const int lane = threadIdx.x & 63;
     // `parts` waves share a row (NONE / GROUP only: nothing is summed along the row), each taking a
     // run of whole 512-element steps; short rows then still give every SIMD enough waves in flight.
     const int64_t gw = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t row = gw / parts;
     if (row >= M) return;  // whole wave leaves together
-    // Side job for the LoRA branch (Alg. 1 "Y_r <- X (L_A L_B)^T" evaluated as (X L_B^T) L_A^T): the
-    // first wave of a row folds the row's split-contraction partials of T = X L_B^T in range order and
-    // stores T as two bf16 planes, hi = bf16(T), lo = bf16(T - hi) (the matrix unit takes bf16 operands;
-    // the pair keeps 16 significant bits). 64 values per row: one per lane.
-    if (lora.T && gw % parts == 0) {
-        // (the loads of up to eight ranges are in flight together; the additions keep the range order)
-        float acc = 0.f;
-        for (int sp0 = 0; sp0 < lora.splits; sp0 += 8) {
-            float p[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                p[u] = sp0 + u < lora.splits ? lora.partials[((int64_t)(sp0 + u) * M + row) * 64 + lane] : 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (sp0 + u < lora.splits) acc += p[u];
-        }
-        const uint32_t hi = f32_to_bf16_rne(acc);
-        lora.T[row * 64 + lane] = (uint16_t)hi;
-        lora.T[(M + row) * 64 + lane] = (uint16_t)f32_to_bf16_rne(acc - __uint_as_float(hi << 16));
-    }
     const int span = ((K + parts - 1) / parts + 511) / 512 * 512;
     const int kbeg = (int)(gw % parts) * span;
     const int kend = min(K, kbeg + span);
@@ -299,11 +279,11 @@ template <bool FP8>
 static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                   float eps, void* vals, uint8_t* meta, uint8_t* vals_km, uint8_t* meta_km,
                                   float* scale, float* rowsums, const float* x_scale, float* fused_scale,
-                                  LoraReduce lora, hipStream_t stream) {
+                                  hipStream_t stream) {
     const int64_t Mpad = kmajor_rows(M);
     if constexpr (!FP8) {
         // only the k-major outputs, nothing summed along a row: the block mapping (see its kernel)
-        if (!vals && !meta && vals_km && meta_km && !lora.T && K % 64 == 0 &&
+        if (!vals && !meta && vals_km && meta_km && K % 64 == 0 &&
             (comp == RTL_COMP_NONE || comp == RTL_COMP_GROUP)) {
             // Blocks per wave: two once the rows are long (measured flat between one and three: at
             // [4096,12288] 190.9 / 190.7 / 190.2 us per rtl_sparse_linear call, at [16896,12288] 817 / 812 /
@@ -334,19 +314,19 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
     switch (comp) {
         case RTL_COMP_NONE:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_NONE, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             break;
         case RTL_COMP_GROUP:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_GROUP, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             break;
         case RTL_COMP_ROW:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_ROW, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             break;
         case RTL_COMP_TENSOR:
             hipLaunchKernelGGL((sparsify_pack_kernel<RTL_COMP_TENSOR, FP8>), grid, block, 0, stream, X, M,
-                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts, lora);
+                               (int)K, ldx, eps, vals, meta, vals_km, meta_km, Mpad, scale, rowsums, x_scale, parts);
             hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps,
                                scale, x_scale, fused_scale);
             break;
@@ -356,10 +336,9 @@ static hipError_t launch_pack_any(const uint16_t* X, int64_t M, int64_t K, int64
 
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                 float eps, uint16_t* vals, uint8_t* meta, uint8_t* vals_km,
-                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream,
-                                LoraReduce lora) {
+                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream) {
     return launch_pack_any<false>(X, M, K, ldx, comp, eps, vals, meta, vals_km, meta_km, scale, rowsums,
-                                  nullptr, nullptr, lora, stream);
+                                  nullptr, nullptr, stream);
 }
 
 hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
@@ -367,7 +346,13 @@ hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int
                                     uint8_t* vals_km, uint8_t* meta_km, float* scale, float* rowsums,
                                     float* fused_scale, hipStream_t stream) {
     return launch_pack_any<true>(X, M, K, ldx, comp, eps, vals8, meta, vals_km, meta_km, scale, rowsums,
-                                 x_scale, fused_scale, LoraReduce{}, stream);
+                                 x_scale, fused_scale, stream);
+}
+
+hipError_t launch_tensor_scale(const float* rowsums, int64_t M, float eps, float* scale, hipStream_t stream) {
+    hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps, scale,
+                       static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
+    return hipGetLastError();
 }
 
 hipError_t launch_quantize_fp8(const uint16_t* W, int64_t rows, int64_t cols, int64_t ld, uint8_t* Wq,

@@ -15,8 +15,8 @@
 //   * two groups of four for the Top-2 selection, whose kept values and positions leave in the k-major
 //     layout the tile loop streams: 32 bytes of values and 4 bytes of metadata per lane and stage,
 //     contiguous over the wave (rows of a 64-k block are 64 and 8 bytes apart).
-// GROUP and NONE scopes only: ROW and TENSOR sum along the whole row, which a split contraction would
-// have to reduce as well; those scopes keep the two-sweep path.
+// ROW and TENSOR scopes sum squares along the whole row; every workgroup leaves the sums of its K range
+// beside its partial plane and lora_reduce_kernel adds them up in range order as well.
 #include "rtl_internal.h"
 #include "select.h"
 
@@ -58,7 +58,8 @@ template <int COMP>
 __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restrict__ X, int64_t M, int KT, int64_t ldx,
                                                            float eps, const uint16_t* __restrict__ LB, int64_t ldlb,
                                                            uint8_t* __restrict__ vals_km, uint8_t* __restrict__ meta_km,
-                                                           int64_t Mpad, float* __restrict__ partials, int per) {
+                                                           int64_t Mpad, float* __restrict__ partials,
+                                                           float* __restrict__ sums, int per) {
     extern __shared__ __align__(16) uint8_t smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restri
     for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    float num = 0.f, den = 0.f;        // ROW / TENSOR: sums of squares of this lane's half of its row, all / kept
 
     const int li = lane & 31, kb = lane >> 5;
     const int64_t row = m0 + wave * 32 + li;             // < Mpad: the k-major buffers are padded to whole 256-row tiles
@@ -134,6 +136,10 @@ __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restri
         for (int s = 0; s < 4; ++s) {
             const GroupOut g0 = select_group<COMP, false>(a[s].u.x, a[s].u.y, eps);
             const GroupOut g1 = select_group<COMP, false>(a[s].u.z, a[s].u.w, eps);
+            if constexpr (COMP == RTL_COMP_ROW || COMP == RTL_COMP_TENSOR) {
+                num += g0.num + g1.num;
+                den += g0.den + g1.den;
+            }
             kept[2 * s] = g0.packed;
             kept[2 * s + 1] = g1.packed;
             nib |= (g0.nibble | (g1.nibble << 4)) << (8 * s);
@@ -154,12 +160,26 @@ __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restri
             const int64_t orow = m0 + wave * 32 + 8 * (r / 4) + 4 * kb + (r % 4);
             if (orow < M) out[orow * kLoraRank + j * 32 + li] = acc[j][r];
         }
+    // ROW / TENSOR: the two lanes of a row add their halves; sums of this K range, [splits][M][2]
+    if constexpr (COMP == RTL_COMP_ROW || COMP == RTL_COMP_TENSOR) {
+        num += __shfl_xor(num, 32, 64);
+        den += __shfl_xor(den, 32, 64);
+        if (kb == 0 && row < M) {
+            float* sd = sums + ((int64_t)split * M + row) * 2;
+            sd[0] = num;
+            sd[1] = den;
+        }
+    }
 }
 
 // Ordered sum of the partial planes, T stored as two bf16 planes [2][M][64]: hi = bf16(T), lo =
-// bf16(T - hi) (the matrix unit takes bf16 operands; the pair keeps 16 significant bits).
+// bf16(T - hi) (the matrix unit takes bf16 operands; the pair keeps 16 significant bits). ROW / TENSOR:
+// the first M threads also add the row sums of the K ranges in order and emit the row's factor
+// s = sqrt(|X|^2 / (|X~|^2 + eps)) (ROW) or the row's two sums for the tensor-wide factor (TENSOR).
 __global__ __launch_bounds__(256) void lora_reduce_kernel(const float* __restrict__ partials, int splits, int64_t M,
-                                                          uint16_t* __restrict__ T) {
+                                                          uint16_t* __restrict__ T, const float* __restrict__ sums,
+                                                          int comp, float eps, float* __restrict__ scale,
+                                                          float* __restrict__ rowsums) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= M * kLoraRank) return;
     float acc = 0.f;
@@ -174,16 +194,33 @@ __global__ __launch_bounds__(256) void lora_reduce_kernel(const float* __restric
     const uint32_t hi = f32_to_bf16_rne(acc);
     T[e] = (uint16_t)hi;
     T[M * kLoraRank + e] = (uint16_t)f32_to_bf16_rne(acc - __uint_as_float(hi << 16));
+    if ((comp == RTL_COMP_ROW || comp == RTL_COMP_TENSOR) && e < M) {
+        float n = 0.f, d = 0.f;
+        for (int sp = 0; sp < splits; ++sp) {
+            n += sums[((int64_t)sp * M + e) * 2];
+            d += sums[((int64_t)sp * M + e) * 2 + 1];
+        }
+        if (comp == RTL_COMP_ROW) {
+            scale[e] = sqrtf(n / (d + eps));
+        } else {
+            rowsums[2 * e] = n;
+            rowsums[2 * e + 1] = d;
+        }
+    }
 }
 
 }  // namespace
 
 hipError_t prepare_pack_lora_kernels() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_NONE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_GROUP>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    hipError_t e = hipSuccess;
+    auto run = [&](const void* k) {
+        if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    };
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_NONE>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_GROUP>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_ROW>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_TENSOR>));
+    return e;
 }
 
 // K ranges of the fused sweep: enough workgroups (128 rows each) to give every compute unit two, at
@@ -201,25 +238,37 @@ static int pack_down_ranges(int64_t M, int64_t K, int* per_out) {
 }
 int pack_down_splits(int64_t M, int64_t K) { return pack_down_ranges(M, K, nullptr); }
 
+size_t pack_down_scratch_bytes(int64_t M, int64_t K) {     // partial planes, then the row sums of the K ranges
+    return (size_t)pack_down_splits(M, K) * (size_t)M * (kLoraRank + 2) * sizeof(float);
+}
+
 hipError_t launch_pack_down(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp, float eps,
-                            const uint16_t* LB, int64_t ldlb, uint8_t* vals_km, uint8_t* meta_km, float* partials,
-                            uint16_t* T, hipStream_t stream) {
+                            const uint16_t* LB, int64_t ldlb, uint8_t* vals_km, uint8_t* meta_km, float* scratch,
+                            uint16_t* T, float* scale, float* rowsums, hipStream_t stream) {
     int per = 1;
     const int splits = pack_down_ranges(M, K, &per);
     const dim3 grid((unsigned)((M + kRows - 1) / kRows), (unsigned)splits);
     const int64_t Mpad = kmajor_rows(M);
-    if (comp == RTL_COMP_GROUP)
-        hipLaunchKernelGGL(pack_down_kernel<RTL_COMP_GROUP>, grid, dim3(256), kLds, stream, X, M, (int)(K / 64), ldx,
-                           eps, LB, ldlb, vals_km, meta_km, Mpad, partials, per);
-    else
-        hipLaunchKernelGGL(pack_down_kernel<RTL_COMP_NONE>, grid, dim3(256), kLds, stream, X, M, (int)(K / 64), ldx,
-                           eps, LB, ldlb, vals_km, meta_km, Mpad, partials, per);
+    float* partials = scratch;
+    float* sums = scratch + (size_t)splits * (size_t)M * kLoraRank;
+#define RTL_PACK_DOWN(C)                                                                                          \
+    hipLaunchKernelGGL(pack_down_kernel<C>, grid, dim3(256), kLds, stream, X, M, (int)(K / 64), ldx, eps, LB, ldlb, \
+                       vals_km, meta_km, Mpad, partials, sums, per)
+    switch (comp) {
+        case RTL_COMP_NONE: RTL_PACK_DOWN(RTL_COMP_NONE); break;
+        case RTL_COMP_GROUP: RTL_PACK_DOWN(RTL_COMP_GROUP); break;
+        case RTL_COMP_ROW: RTL_PACK_DOWN(RTL_COMP_ROW); break;
+        case RTL_COMP_TENSOR: RTL_PACK_DOWN(RTL_COMP_TENSOR); break;
+    }
+#undef RTL_PACK_DOWN
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t n = M * kLoraRank;
     hipLaunchKernelGGL(lora_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, partials, splits,
-                       M, T);
-    return hipGetLastError();
+                       M, T, sums, (int)comp, eps, scale, rowsums);
+    e = hipGetLastError();
+    if (e != hipSuccess || comp != RTL_COMP_TENSOR) return e;
+    return launch_tensor_scale(rowsums, M, eps, scale, stream);
 }
 
 }  // namespace rtl

@@ -31,17 +31,9 @@ inline size_t kmajor_val_bytes(int64_t M, int64_t K, size_t val_bytes) {
 // Launches the select/compensate/compress sweep. The canonical outputs (`vals`, `meta`) and the
 // k-major ones (`vals_km`, `meta_km`, need K % 64 == 0) are each optional; `rowsums` ([M][2] fp32)
 // is only touched for RTL_COMP_TENSOR. Returns the HIP launch status.
-// `lora` (optional side job of the sweep, LoRA branch only): fold the `splits` fp32 partial planes
-// [splits][M][64] of T = X L_B^T in range order and store T as two bf16 planes [2][M][64] (hi, lo).
-struct LoraReduce {
-    const float* partials = nullptr;
-    int splits = 0;
-    uint16_t* T = nullptr;
-};
 hipError_t launch_sparsify_pack(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp,
                                 float eps, uint16_t* vals, uint8_t* meta, uint8_t* vals_km,
-                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream,
-                                LoraReduce lora = LoraReduce{});
+                                uint8_t* meta_km, float* scale, float* rowsums, hipStream_t stream);
 // FP8 form (implementation details, "orthogonal validation with FP8 quantization"): kept values
 // leave as E4M3 codes of (s * x) / x_scale[0] (vals8 [M,K/2] bytes); `meta_km` then uses the 16-byte
 // records and `vals_km` 128-k blocks (need K % 128 == 0). `fused_scale` (nullable, [1]) receives
@@ -69,7 +61,6 @@ struct GemmArgs {
     const float* row_scale; // nullable [M]
     const float* tensor_scale; // nullable [1]
     uint16_t* Y;            // [M,N] (ldy)
-    float* partials;        // split contraction: fp32 partial results [splits][M][N]
     int64_t M, N, K, lda, ldw, ldy;
     // LoRA tail of the sparse kernel (Alg. 1 "Y_r <- X (L_A L_B)^T" as (X L_B^T) L_A^T):
     const uint16_t* T;      // nullable: X L_B^T as two bf16 planes (hi, lo), [2][M,64]
@@ -80,7 +71,6 @@ struct GemmArgs {
     int64_t t_plane;        // LoRA: elements between the hi and lo planes of T (M of the whole activation * 64)
     int64_t m_split;        // rows [0, m_split) are cut into body tiles, rows [m_split, M) into 256 x 128 tail tiles
     int body_tiles, tail_tiles;
-    int splits;             // split contraction: number of K ranges (grid.y)
     bool fp8;               // sparse only: E4M3 operands, K % 128 == 0, 16-byte metadata records
 };
 size_t gemm_workspace_bytes(bool sparse, int64_t M, int64_t N, int64_t K);
@@ -94,25 +84,20 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a, hipStream_t stream);
 // by body tiles, number of body tiles, number of 256 x 128 tail tiles}. Host arithmetic only.
 void tile_plan(int64_t M, int64_t N, bool dense, int64_t out[4]);
 
-// LoRA down-projection as a sweep of its own (ROW / TENSOR scopes; NONE / GROUP use launch_pack_down
-// below): split-K partial products of T = X L_B^T into `partials` ([splits][M][64] fp32, splits =
-// lora_down_splits(M, K)). The ordered reduction to the bf16 hi/lo planes rides on the pack sweep that
-// follows (LoraReduce above).
 constexpr int kLoraRank = 64;
-int lora_down_splits(int64_t M, int64_t K);
-size_t lora_down_partial_bytes(int64_t M, int64_t K);
-hipError_t launch_lora_down(const uint16_t* X, int64_t ldx, const uint16_t* LB, int64_t ldlb, int64_t M,
-                            int64_t K, float* partials, hipStream_t stream);
 
-// One pass over X for the LoRA branch (pack_lora.hip; GROUP and NONE scopes): the sweep writes the k-major
-// compressed operand (as launch_sparsify_pack does) and the fp32 partial planes of T = X L_B^T
-// ([pack_down_splits(M, K)][M][64]), then a second small kernel sums the planes in range order into the
-// two bf16 planes of T ([2][M][64]: hi, lo).
-int pack_down_splits(int64_t M, int64_t K);
+// One pass over X for the LoRA branch (pack_lora.hip): the sweep writes the k-major compressed operand (as
+// launch_sparsify_pack does) and, per K range, an fp32 partial plane of T = X L_B^T and (ROW / TENSOR) the
+// row sums of squares, into `scratch` (pack_down_scratch_bytes(M, K) bytes); a second small kernel adds the
+// ranges up in order into the two bf16 planes of T ([2][M][64]: hi, lo), the ROW factors `scale` [M] or
+// the TENSOR row sums `rowsums` [M][2], from which launch_tensor_scale then forms scale[0].
+size_t pack_down_scratch_bytes(int64_t M, int64_t K);
 hipError_t prepare_pack_lora_kernels();
 hipError_t launch_pack_down(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp, float eps,
-                            const uint16_t* LB, int64_t ldlb, uint8_t* vals_km, uint8_t* meta_km, float* partials,
-                            uint16_t* T, hipStream_t stream);
+                            const uint16_t* LB, int64_t ldlb, uint8_t* vals_km, uint8_t* meta_km, float* scratch,
+                            uint16_t* T, float* scale, float* rowsums, hipStream_t stream);
+// TENSOR scope: the single factor from the per-row sums [M][2] (fixed order, fp64), into scale[0].
+hipError_t launch_tensor_scale(const float* rowsums, int64_t M, float eps, float* scale, hipStream_t stream);
 
 // ---- diagnostics (diag.hip) -------------------------------------------------------------------
 // Issue-rate probe: `blocks` workgroups of four waves, each wave issuing 4 * iters matrix
