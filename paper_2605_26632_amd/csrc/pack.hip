@@ -198,9 +198,19 @@ __global__ __launch_bounds__(256) void tensor_scale_kernel(const float* __restri
                                                            float* __restrict__ fused) {
     __shared__ double sn[256], sd[256];
     double n = 0.0, d = 0.0;
-    for (int64_t r = threadIdx.x; r < M; r += 256) {
-        n += (double)rowsums[2 * r];
-        d += (double)rowsums[2 * r + 1];
+    const float2* rs = reinterpret_cast<const float2*>(rowsums);
+    int64_t r = threadIdx.x;
+    for (; r + 3 * 256 < M; r += 4 * 256) {     // four loads in flight; the additions keep the row order of a thread
+        const float2 v0 = rs[r], v1 = rs[r + 256], v2 = rs[r + 512], v3 = rs[r + 768];
+        n += (double)v0.x; d += (double)v0.y;
+        n += (double)v1.x; d += (double)v1.y;
+        n += (double)v2.x; d += (double)v2.y;
+        n += (double)v3.x; d += (double)v3.y;
+    }
+    for (; r < M; r += 256) {
+        const float2 v = rs[r];
+        n += (double)v.x;
+        d += (double)v.y;
     }
     sn[threadIdx.x] = n;
     sd[threadIdx.x] = d;
