@@ -97,7 +97,7 @@ const char* rtl_status_str(rtl_status s) {
     return "RTL_ERR_UNKNOWN";
 }
 
-const char* rtl_version(void) { return "rtlynx-gfx950 0.2"; }
+const char* rtl_version(void) { return "rtlynx-gfx950 0.3"; }
 
 rtl_status rtl_init(void) { return device_ready(); }
 
