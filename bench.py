@@ -412,7 +412,13 @@ def main():
         t_fp8 = event_times(lambda: rtl.sparse_linear_fp8(X, Wq, xs8, comp=comp, out=Y, ws=ws8), n_ev, 10, torch)
         t_pack8 = event_times(lambda: rtl.sparsify_pack_fp8(X, xs8, comp=comp, out=(v8, m8)), n_ev, 10, torch)
         fp8_ms, pack8_ms = sum(t_fp8) / len(t_fp8), sum(t_pack8) / len(t_pack8)
+        LA8, LB8 = synth.lora(N, K, 64, seed=3, device=dev)
+        ws8l = torch.empty(rtl.sparse_lora_linear_fp8_workspace(M, N, K, 64, comp) + 256, dtype=torch.uint8, device=dev)
+        t_fp8l = event_times(lambda: rtl.sparse_lora_linear_fp8(X, Wq, xs8, LA8, LB8, comp=comp, out=Y, ws=ws8l),
+                             n_ev, 10, torch)
+        fp8l_ms = sum(t_fp8l) / len(t_fp8l)
         fp8 = {"ms_per_step": round(fp8_ms, 4), "tflops": round(flops / (fp8_ms * 1e-3) / 1e12, 1),
+               "with_lora_r64_ms": round(fp8l_ms, 4), "lora_overhead": round(fp8l_ms / fp8_ms - 1.0, 4),
                "pack_ms": round(pack8_ms, 4), "gemm_ms": round(fp8_ms - pack8_ms, 4),
                "gemm_tflops": round(flops / ((fp8_ms - pack8_ms) * 1e-3) / 1e12, 1),
                "speedup_vs_bf16_sparse_linear": None, "hipblaslt_fp8_dense_ms": None}

@@ -233,6 +233,21 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
                                  rtl_comp comp, float eps,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* rtl_sparse_lora_linear_fp8 - the whole of Alg. 1 on FP8 operands (the "W8A8 + RT-Lynx" rows of the
+ * orthogonality tables): Y = f * (Q Wq^T) + X (L_A L_B)^T (+ b), the sparse product as in
+ * rtl_sparse_linear_fp8, the LoRA residual as in rtl_sparse_lora_linear: it looks at the bf16 input,
+ * its factors stay bf16, and it is added in fp32 to the dequantised sparse product before the single
+ * bf16 rounding of Y. One sweep over X writes the FP8 compressed operand and forms X L_B^T.
+ *   Arguments as for rtl_sparse_linear_fp8 plus LA, LB, R, ldla, ldlb as for rtl_sparse_lora_linear.
+ *   workspace  rtl_sparse_lora_linear_fp8_workspace(M, N, K, R, comp) bytes, 256-byte aligned. */
+size_t rtl_sparse_lora_linear_fp8_workspace(int64_t M, int64_t N, int64_t K, int64_t R, rtl_comp comp);
+rtl_status rtl_sparse_lora_linear_fp8(const void* X, const void* Wq, const float* x_scale,
+                                      const void* LA, const void* LB, const void* bias, void* Y,
+                                      int64_t M, int64_t N, int64_t K, int64_t R,
+                                      int64_t ldx, int64_t ldw, int64_t ldla, int64_t ldlb, int64_t ldy,
+                                      rtl_comp comp, float eps,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * rtl_diag_matrix_rate - diagnostic, not a step of the method: measures the issue rate of the matrix
  * instruction the linears are built on with nothing else running (operands in registers), so that a

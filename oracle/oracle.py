@@ -279,3 +279,17 @@ def sparse_linear_fp8_oracle(X, Wq, x_scale, bias=None, scope=GROUP, eps=1e-8, r
             Y[rows[1]:] = 0
     r["Y"] = Y.astype(np.float32)
     return r
+
+
+def sparse_lora_linear_fp8_oracle(X, Wq, x_scale, LA, LB, bias=None, scope=GROUP, eps=1e-8, delta=None):
+    """The whole of Alg. 1 on FP8 operands: the W8A8 sparse product of sparse_linear_fp8_oracle plus the
+    LoRA residual X (L_A L_B)^T of sparse_lora_linear_oracle (bf16 input, bf16 factors, fp32), fp32 [M,N].
+    Returns the FP8 oracle's dict with Y_s (sparse product, bias included), Y_r and Y = Y_s + Y_r."""
+    r = sparse_linear_fp8_oracle(X, Wq, x_scale, bias, scope, eps)
+    D = lora_delta(LA, LB) if delta is None else delta
+    Yr = linear_f32w(bf16_to_f32(_u16(X)), D)
+    Y = np.empty_like(Yr)
+    _lib.orc_add(_ptr(r["Y"]), _ptr(Yr), Yr.size, _ptr(Y))
+    r["Y_s"], r["Y_r"], r["Y"] = r["Y"], Yr, Y
+    return r
+

@@ -21,6 +21,7 @@ SYMBOLS = ["rtl_sparsify_pack_workspace", "rtl_sparsify_pack", "rtl_packed_linea
            "rtl_dense_linear_workspace", "rtl_dense_linear",
            "rtl_quantize_fp8", "rtl_sparsify_pack_fp8_workspace", "rtl_sparsify_pack_fp8",
            "rtl_sparse_linear_fp8_workspace", "rtl_sparse_linear_fp8",
+           "rtl_sparse_lora_linear_fp8_workspace", "rtl_sparse_lora_linear_fp8",
            "rtl_diag_matrix_rate", "rtl_diag_fill_rate", "rtl_diag_pack_sweep", "rtl_diag_tile_plan", "rtl_init", "rtl_status_str", "rtl_version"]
 
 _lib = None
@@ -78,6 +79,11 @@ def lib():
         L.rtl_diag_matrix_rate.restype = ci
         L.rtl_diag_fill_rate.argtypes = [vp, sz, i64, ci, vp, vp, vp]
         L.rtl_diag_fill_rate.restype = ci
+        L.rtl_sparse_lora_linear_fp8_workspace.argtypes = [i64, i64, i64, i64, ci]
+        L.rtl_sparse_lora_linear_fp8_workspace.restype = sz
+        L.rtl_sparse_lora_linear_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, i64,
+                                                 i64, ci, fl, vp, sz, vp]
+        L.rtl_sparse_lora_linear_fp8.restype = ci
         L.rtl_diag_pack_sweep.argtypes = [vp, i64, i64, i64, ci, fl, vp, sz, vp]
         L.rtl_diag_pack_sweep.restype = ci
         L.rtl_diag_tile_plan.argtypes = [i64, i64, ci, C.POINTER(C.c_int64)]
@@ -291,6 +297,29 @@ def sparse_linear_fp8(X, Wq, x_scale, bias=None, comp=COMP_GROUP, eps=1e-8, out=
     st = L.rtl_sparse_linear_fp8(_p(X), _p(Wq), _p(x_scale), _p(bias), _p(Y), M, N, K, X.stride(0),
                                  Wq.stride(0), Y.stride(0), comp, eps, _p(ws), ws.numel(), _stream())
     _check(st, "rtl_sparse_linear_fp8")
+    return Y
+
+
+def sparse_lora_linear_fp8_workspace(M, N, K, R=64, comp=COMP_GROUP):
+    return int(lib().rtl_sparse_lora_linear_fp8_workspace(M, N, K, R, comp))
+
+
+def sparse_lora_linear_fp8(X, Wq, x_scale, LA, LB, bias=None, comp=COMP_GROUP, eps=1e-8, out=None, ws=None):
+    """rtl_sparse_lora_linear_fp8: Y = x_scale * (e4m3(S(X) / x_scale) Wq^T) + X (L_A L_B)^T (+ bias), bf16 [M,N]."""
+    _need_cuda(X, Wq, x_scale, LA, LB)
+    assert Wq.dtype == torch.uint8 and x_scale.dtype == torch.float32
+    assert LA.dtype == torch.bfloat16 and LB.dtype == torch.bfloat16
+    M, K = X.shape
+    N, R = LA.shape
+    assert Wq.shape == (N, K) and LB.shape == (R, K)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device) if out is None else out
+    L = lib()
+    if ws is None:
+        ws = _ws(L.rtl_sparse_lora_linear_fp8_workspace(M, N, K, R, comp), X.device)
+    st = L.rtl_sparse_lora_linear_fp8(_p(X), _p(Wq), _p(x_scale), _p(LA), _p(LB), _p(bias), _p(Y), M, N, K, R,
+                                      X.stride(0), Wq.stride(0), LA.stride(0), LB.stride(0), Y.stride(0), comp, eps,
+                                      _p(ws), ws.numel(), _stream())
+    _check(st, "rtl_sparse_lora_linear_fp8")
     return Y
 
 

@@ -381,6 +381,59 @@ rtl_status rtl_sparse_linear_fp8(const void* X, const void* Wq, const float* x_s
     return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
 }
 
+// rtl_sparse_lora_linear_fp8 workspace: [rtl_sparse_linear_fp8 workspace | T as two bf16 planes | sweep scratch]
+size_t rtl_sparse_lora_linear_fp8_workspace(int64_t M, int64_t N, int64_t K, int64_t R, rtl_comp comp) {
+    if (M <= 0 || N <= 0 || K <= 0 || R != rtl::kLoraRank || !comp_ok(comp)) return 0;
+    return sparse_ws(M, N, K, comp, 1).total + round_up((size_t)M * rtl::kLoraRank * 4, 256) +
+           round_up(rtl::pack_down_scratch_bytes(M, K), 256);
+}
+
+rtl_status rtl_sparse_lora_linear_fp8(const void* X, const void* Wq, const float* x_scale, const void* LA,
+                                      const void* LB, const void* bias, void* Y, int64_t M, int64_t N, int64_t K,
+                                      int64_t R, int64_t ldx, int64_t ldw, int64_t ldla, int64_t ldlb, int64_t ldy,
+                                      rtl_comp comp, float eps, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+    if (!comp_ok(comp) || !eps_ok(eps)) return RTL_ERR_ARG;
+    if (R != rtl::kLoraRank || ldla < R || ldlb < K) return RTL_ERR_SHAPE;
+    rtl_status st = check_linear(X, Wq, Y, M, N, K, ldx, ldw, ldy, K, 128, 16);
+    if (st != RTL_OK || M == 0 || N == 0) return st;
+    if (!x_scale || !LA || !LB) return RTL_ERR_NULL;
+    if (ldla % 8 != 0 || ldlb % 8 != 0 || !aligned(LA, 16) || !aligned(LB, 16) || (bias && !aligned(bias, 2)) ||
+        !aligned(x_scale, 4))
+        return RTL_ERR_ALIGN;
+    const SparseWs ws = sparse_ws(M, N, K, comp, 1);
+    const size_t t_off = ws.total, p_off = t_off + round_up((size_t)M * rtl::kLoraRank * 4, 256);
+    const size_t need = p_off + round_up(rtl::pack_down_scratch_bytes(M, K), 256);
+    if (!workspace || workspace_bytes < need) return RTL_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return RTL_ERR_ALIGN;
+    RTL_REQUIRE_DEVICE();
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    float* scale = reinterpret_cast<float*>(base + ws.scale);
+    float* fused = scale + (comp == RTL_COMP_ROW ? M : 1);   // x_scale times the TENSOR factor
+    uint16_t* T = reinterpret_cast<uint16_t*>(base + t_off);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = rtl::launch_pack_down(static_cast<const uint16_t*>(X), M, K, ldx, comp, eps,
+                                         static_cast<const uint16_t*>(LB), ldlb, base + ws.vals, base + ws.meta,
+                                         reinterpret_cast<float*>(base + p_off), T, scale,
+                                         reinterpret_cast<float*>(base + ws.pack), s, x_scale, fused);
+    if (e != hipSuccess) return RTL_ERR_HIP;
+    rtl::GemmArgs g{};
+    g.fp8 = true;
+    g.A = base + ws.vals;
+    g.meta = base + ws.meta;
+    g.W = Wq;
+    g.bias = static_cast<const uint16_t*>(bias);
+    g.row_scale = comp == RTL_COMP_ROW ? scale : nullptr;
+    g.tensor_scale = comp == RTL_COMP_TENSOR ? fused : x_scale;   // dequantisation of the sparse product only
+    g.Y = static_cast<uint16_t*>(Y);
+    g.M = M; g.N = N; g.K = K; g.lda = 0; g.ldw = ldw; g.ldy = ldy;
+    g.T = T;
+    g.LA = static_cast<const uint16_t*>(LA);
+    g.ldla = ldla;
+    e = rtl::launch_gemm(true, g, s);
+    return e == hipSuccess ? RTL_OK : RTL_ERR_HIP;
+}
+
 rtl_status rtl_diag_matrix_rate(int kind, const void* operands, int64_t iters, int blocks,
                                 uint64_t* clocks, float* sink, void* stream) {
     if (kind < 0 || kind > 1) return RTL_ERR_ARG;

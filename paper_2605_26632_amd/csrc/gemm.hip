@@ -167,7 +167,7 @@ template <bool SPARSE, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int
 __device__ __forceinline__ void gemm_tile(const GemmArgs a, const int tile) {
     static_assert(!D64 || (!SPARSE && MODE != 1), "64-k stages: dense kernels only");
     static_assert(MODE == 0 || (MODE == 1 && SPARSE), "mode/operand combination");
-    static_assert(!FP8 || (SPARSE && MODE == 0), "FP8 operands: plain sparse kernel only");
+    static_assert(!FP8 || SPARSE, "FP8 operands: sparse kernels only");
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -861,6 +861,8 @@ hipError_t prepare_gemm_kernels() {
     auto run = [&](hipError_t r) { if (e == hipSuccess) e = r; };
     run(Mixed<true, 192, 4, 2, 3, 0, true>::prepare());
     run(Mixed<true, 256, 2, 4, 3, 0, true>::prepare());
+    run(Mixed<true, 192, 4, 2, 3, 1, true>::prepare());
+    run(Mixed<true, 256, 2, 4, 3, 1, true>::prepare());
     run(Mixed<true, 192, 4, 2, 3, 1>::prepare());
     run(Mixed<true, 192, 4, 2, 3>::prepare());
     run(Mixed<true, 256, 2, 4, 3, 1>::prepare());
@@ -879,6 +881,10 @@ hipError_t launch_gemm(bool sparse, const GemmArgs& a_in, hipStream_t stream) {
     a.rows_pad = kmajor_rows(a.M);
     a.t_plane = a.M * kLoraRank;
     if (sparse && a.fp8) {
+        if (a.T != nullptr) {          // LoRA tail in bf16 on top of the FP8 product
+            if (plan.use_192) return Mixed<true, 192, 4, 2, 3, 1, true>::launch(a, stream);
+            return Mixed<true, 256, 2, 4, 3, 1, true>::launch(a, stream);
+        }
         if (plan.use_192) return Mixed<true, 192, 4, 2, 3, 0, true>::launch(a, stream);
         return Mixed<true, 256, 2, 4, 3, 0, true>::launch(a, stream);
     }

@@ -359,9 +359,9 @@ hipError_t launch_sparsify_pack_fp8(const uint16_t* X, int64_t M, int64_t K, int
                                  x_scale, fused_scale, stream);
 }
 
-hipError_t launch_tensor_scale(const float* rowsums, int64_t M, float eps, float* scale, hipStream_t stream) {
-    hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps, scale,
-                       static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
+hipError_t launch_tensor_scale(const float* rowsums, int64_t M, float eps, float* scale, hipStream_t stream,
+                               const float* mul, float* fused) {
+    hipLaunchKernelGGL(tensor_scale_kernel, dim3(1), dim3(256), 0, stream, rowsums, M, eps, scale, mul, fused);
     return hipGetLastError();
 }
 

@@ -54,9 +54,12 @@ __device__ __forceinline__ void wait_vm() {   // at most N loads of this wave ou
     __builtin_amdgcn_s_waitcnt(0x0070 | (N & 0xF) | ((N >> 4) << 14));
 }
 
-template <int COMP>
+// FP8: the kept values leave as E4M3 codes of (s x) / x_scale[0] in the FP8 form of the k-major layout
+// (blocks of 128 dense k: 64 codes and a 16-byte metadata record per row; a stage is half a block).
+template <int COMP, bool FP8>
 __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restrict__ X, int64_t M, int KT, int64_t ldx,
-                                                           float eps, const uint16_t* __restrict__ LB, int64_t ldlb,
+                                                           float eps, const float* __restrict__ x_scale,
+                                                           const uint16_t* __restrict__ LB, int64_t ldlb,
                                                            uint8_t* __restrict__ vals_km, uint8_t* __restrict__ meta_km,
                                                            int64_t Mpad, float* __restrict__ partials,
                                                            float* __restrict__ sums, int per) {
@@ -104,8 +107,10 @@ __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restri
 
     const int li = lane & 31, kb = lane >> 5;
     const int64_t row = m0 + wave * 32 + li;             // < Mpad: the k-major buffers are padded to whole 256-row tiles
-    uint8_t* vrow = vals_km + ((int64_t)kt0 * Mpad + row) * 64 + kb * 32;
+    uint8_t* vrow = vals_km + ((int64_t)kt0 * Mpad + row) * 64 + kb * 32;      // bf16 form
     uint8_t* mrow = meta_km + ((int64_t)kt0 * Mpad + row) * 8 + kb * 4;
+    float inv = 1.0f;
+    if constexpr (FP8) inv = 1.0f / x_scale[0];
 
     // ---- prologue: two stages in flight ---------------------------------------------------------------
     request(0);
@@ -134,8 +139,8 @@ __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restri
         uint32_t kept[8], nib = 0;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const GroupOut g0 = select_group<COMP, false>(a[s].u.x, a[s].u.y, eps);
-            const GroupOut g1 = select_group<COMP, false>(a[s].u.z, a[s].u.w, eps);
+            const GroupOut g0 = select_group<COMP, FP8>(a[s].u.x, a[s].u.y, eps, inv);
+            const GroupOut g1 = select_group<COMP, FP8>(a[s].u.z, a[s].u.w, eps, inv);
             if constexpr (COMP == RTL_COMP_ROW || COMP == RTL_COMP_TENSOR) {
                 num += g0.num + g1.num;
                 den += g0.den + g1.den;
@@ -144,10 +149,21 @@ __global__ __launch_bounds__(256) void pack_down_kernel(const uint16_t* __restri
             kept[2 * s + 1] = g1.packed;
             nib |= (g0.nibble | (g1.nibble << 4)) << (8 * s);
         }
-        uint8_t* vdst = vrow + (int64_t)st * Mpad * 64;
-        *reinterpret_cast<uint4*>(vdst) = make_uint4(kept[0], kept[1], kept[2], kept[3]);
-        *reinterpret_cast<uint4*>(vdst + 16) = make_uint4(kept[4], kept[5], kept[6], kept[7]);
-        *reinterpret_cast<uint32_t*>(mrow + (int64_t)st * Mpad * 8) = nib;
+        if constexpr (FP8) {
+            // stage kt0 + st is half `h` of the 128-k block (kt0 + st) / 2: 16 codes at 32 h + 16 kb of the
+            // row's 64, 4 metadata bytes at 8 h + 4 kb of its 16
+            const int kt = kt0 + st, h = kt & 1;
+            const int64_t rec = (int64_t)(kt >> 1) * Mpad + row;
+            *reinterpret_cast<uint4*>(vals_km + rec * 64 + h * 32 + kb * 16) =
+                make_uint4(kept[0] | (kept[1] << 16), kept[2] | (kept[3] << 16), kept[4] | (kept[5] << 16),
+                           kept[6] | (kept[7] << 16));
+            *reinterpret_cast<uint32_t*>(meta_km + rec * 16 + h * 8 + kb * 4) = nib;
+        } else {
+            uint8_t* vdst = vrow + (int64_t)st * Mpad * 64;
+            *reinterpret_cast<uint4*>(vdst) = make_uint4(kept[0], kept[1], kept[2], kept[3]);
+            *reinterpret_cast<uint4*>(vdst + 16) = make_uint4(kept[4], kept[5], kept[6], kept[7]);
+            *reinterpret_cast<uint32_t*>(mrow + (int64_t)st * Mpad * 8) = nib;
+        }
     }
 
     // ---- fp32 partial plane of this K range: register r of a lane is row 8 (r / 4) + 4 kb + r % 4 of
@@ -216,10 +232,14 @@ hipError_t prepare_pack_lora_kernels() {
     auto run = [&](const void* k) {
         if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     };
-    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_NONE>));
-    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_GROUP>));
-    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_ROW>));
-    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_TENSOR>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_NONE, false>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_GROUP, false>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_ROW, false>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_TENSOR, false>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_NONE, true>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_GROUP, true>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_ROW, true>));
+    run(reinterpret_cast<const void*>(pack_down_kernel<RTL_COMP_TENSOR, true>));
     return e;
 }
 
@@ -244,16 +264,24 @@ size_t pack_down_scratch_bytes(int64_t M, int64_t K) {     // partial planes, th
 
 hipError_t launch_pack_down(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp, float eps,
                             const uint16_t* LB, int64_t ldlb, uint8_t* vals_km, uint8_t* meta_km, float* scratch,
-                            uint16_t* T, float* scale, float* rowsums, hipStream_t stream) {
+                            uint16_t* T, float* scale, float* rowsums, hipStream_t stream, const float* x_scale,
+                            float* fused_scale) {
     int per = 1;
     const int splits = pack_down_ranges(M, K, &per);
     const dim3 grid((unsigned)((M + kRows - 1) / kRows), (unsigned)splits);
     const int64_t Mpad = kmajor_rows(M);
     float* partials = scratch;
     float* sums = scratch + (size_t)splits * (size_t)M * kLoraRank;
-#define RTL_PACK_DOWN(C)                                                                                          \
-    hipLaunchKernelGGL(pack_down_kernel<C>, grid, dim3(256), kLds, stream, X, M, (int)(K / 64), ldx, eps, LB, ldlb, \
-                       vals_km, meta_km, Mpad, partials, sums, per)
+    const bool fp8 = x_scale != nullptr;
+#define RTL_PACK_DOWN(C)                                                                                              \
+    do {                                                                                                              \
+        if (fp8)                                                                                                      \
+            hipLaunchKernelGGL((pack_down_kernel<C, true>), grid, dim3(256), kLds, stream, X, M, (int)(K / 64), ldx,  \
+                               eps, x_scale, LB, ldlb, vals_km, meta_km, Mpad, partials, sums, per);                  \
+        else                                                                                                          \
+            hipLaunchKernelGGL((pack_down_kernel<C, false>), grid, dim3(256), kLds, stream, X, M, (int)(K / 64), ldx, \
+                               eps, x_scale, LB, ldlb, vals_km, meta_km, Mpad, partials, sums, per);                  \
+    } while (0)
     switch (comp) {
         case RTL_COMP_NONE: RTL_PACK_DOWN(RTL_COMP_NONE); break;
         case RTL_COMP_GROUP: RTL_PACK_DOWN(RTL_COMP_GROUP); break;
@@ -268,7 +296,7 @@ hipError_t launch_pack_down(const uint16_t* X, int64_t M, int64_t K, int64_t ldx
                        M, T, sums, (int)comp, eps, scale, rowsums);
     e = hipGetLastError();
     if (e != hipSuccess || comp != RTL_COMP_TENSOR) return e;
-    return launch_tensor_scale(rowsums, M, eps, scale, stream);
+    return launch_tensor_scale(rowsums, M, eps, scale, stream, x_scale, fused_scale);
 }
 
 }  // namespace rtl

@@ -95,9 +95,14 @@ size_t pack_down_scratch_bytes(int64_t M, int64_t K);
 hipError_t prepare_pack_lora_kernels();
 hipError_t launch_pack_down(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, rtl_comp comp, float eps,
                             const uint16_t* LB, int64_t ldlb, uint8_t* vals_km, uint8_t* meta_km, float* scratch,
-                            uint16_t* T, float* scale, float* rowsums, hipStream_t stream);
-// TENSOR scope: the single factor from the per-row sums [M][2] (fixed order, fp64), into scale[0].
-hipError_t launch_tensor_scale(const float* rowsums, int64_t M, float eps, float* scale, hipStream_t stream);
+                            uint16_t* T, float* scale, float* rowsums, hipStream_t stream,
+                            const float* x_scale = nullptr, float* fused_scale = nullptr);
+// (x_scale set: FP8 form: kept values as E4M3 codes of (s x) / x_scale[0] in the FP8 k-major layout, K % 128 == 0;
+//  fused_scale [1] then receives x_scale[0] times the TENSOR factor, TENSOR scope only.)
+// TENSOR scope: the single factor from the per-row sums [M][2] (fixed order, fp64), into scale[0]; `fused`
+// (nullable) receives scale[0] * mul[0].
+hipError_t launch_tensor_scale(const float* rowsums, int64_t M, float eps, float* scale, hipStream_t stream,
+                               const float* mul = nullptr, float* fused = nullptr);
 
 // ---- diagnostics (diag.hip) -------------------------------------------------------------------
 // Issue-rate probe: `blocks` workgroups of four waves, each wave issuing 4 * iters matrix

@@ -407,3 +407,26 @@ def test_fp8_sparse_linear_reduces_to_integer_matmul_and_fp64():
     y16 = oracle.sparse_linear_oracle(Xb, Wb, scope=oracle.GROUP)["Y"]
     y8 = oracle.sparse_linear_fp8_oracle(Xb, Wq, x_scale, scope=oracle.GROUP)["Y"]
     assert oracle.rfe(y16, y8) < 0.1
+
+
+def test_fp8_lora_composition_is_the_sum_of_its_two_pinned_parts():
+    """sparse_lora_linear_fp8_oracle: the W8A8 sparse product (pinned above) plus the LoRA residual of the
+    bf16 input (pinned above), nothing else: checked against both parts, against an fp64 evaluation of the
+    residual, and with a zero factor."""
+    X, W = synth.workload("tiny", seed=15, M=48)
+    LA, LB = synth.lora(W.shape[0], W.shape[1], 16, seed=16, std_a=0.5, std_b=0.5)
+    Xb, Wb, LAb, LBb = (synth.bits(t) for t in (X, W, LA, LB))
+    Wq = oracle.quantize_weights_fp8(Wb)
+    xs = float(np.abs(oracle.bf16_to_f32(Xb)).max() * 2 ** 0.5 / 448.0)
+    b = synth.bits(synth.bias(W.shape[0], seed=17))
+    for scope in (oracle.NONE, oracle.GROUP, oracle.ROW, oracle.TENSOR):
+        r = oracle.sparse_lora_linear_fp8_oracle(Xb, Wq, xs, LAb, LBb, bias=b, scope=scope)
+        base = oracle.sparse_linear_fp8_oracle(Xb, Wq, xs, bias=b, scope=scope)["Y"]
+        assert np.array_equal(r["Y_s"], base)
+        Xf = oracle.bf16_to_f32(Xb).astype(np.float64)
+        ref_r = Xf @ (oracle.bf16_to_f32(LAb).astype(np.float64) @ oracle.bf16_to_f32(LBb).astype(np.float64)).T
+        assert np.allclose(r["Y_r"], ref_r, rtol=0, atol=3e-5 * np.abs(ref_r).max())
+        assert np.allclose(r["Y"], base.astype(np.float64) + ref_r, rtol=0, atol=3e-5 * np.abs(ref_r).max() + 1e-6 * np.abs(base).max())
+        r0 = oracle.sparse_lora_linear_fp8_oracle(Xb, Wq, xs, np.zeros_like(LAb), LBb, bias=b, scope=scope)
+        assert np.array_equal(r0["Y"], base)
+

@@ -460,6 +460,73 @@ def test_linears_on_strided_views(comp):
         assert (bigY[:, :16] == 7.0).all() and (bigY[:, 16 + N:] == 7.0).all()
 
 
+# ------------------------------------------------------------------ FP8 + LoRA (whole Alg. 1 on FP8 operands)
+@pytest.mark.parametrize("comp", COMPS)
+def test_sparse_lora_linear_fp8_tiny_config(comp):
+    """rtl_sparse_lora_linear_fp8 against the oracle's composition: the benchmark spec's bound, and elementwise
+    with the allowance of the FP8 product (the instruction's cut, computed from the operands of every
+    run) plus one bf16 rounding of the sum; with a zero L_A the call must equal rtl_sparse_linear_fp8 bit
+    for bit (same sweep outputs, same tile loop, a tail that adds zeros)."""
+    X, W = synth.workload("tiny", seed=2, device=DEV)
+    N, K = W.shape
+    LA, LB = synth.lora(N, K, 64, seed=33, device=DEV, std_a=0.05, std_b=0.05)
+    b = synth.bias(N, seed=34, device=DEV)
+    xs = fp8_scale(X)
+    Wq = rtl.quantize_fp8(W)
+    Y = rtl.sparse_lora_linear_fp8(X, Wq, xs, LA, LB, bias=b, comp=comp)
+    r = oracle.sparse_lora_linear_fp8_oracle(synth.bits(X), Wq.cpu().numpy(), float(xs.item()), synth.bits(LA),
+                                             synth.bits(LB), bias=synth.bits(b), scope=comp)
+    y, ref = y_to_np(Y).astype(np.float64), r["Y"].astype(np.float64)
+    assert rel_max_err(y, ref) <= Y_TOL
+    assert rel_max_err(r["Y_s"], r["Y"]) > 5 * Y_TOL          # the residual matters at this scale
+    f = float(xs.item()) * (r["s"].astype(np.float64)[:, None] if comp == rtl.COMP_ROW else
+                            (float(r["s"][0]) if comp == rtl.COMP_TENSOR else 1.0))
+    f = np.abs(np.asarray(f, dtype=np.float64))
+    Wq_np = Wq.cpu().numpy()
+    Qa = np.abs(oracle.e4m3_decode(r["Q"])).astype(np.float64)
+    Wa = np.abs(oracle.e4m3_decode(Wq_np)).astype(np.float64)
+    bound = (2.0 ** -8 * np.abs(ref) + f * fp8_truncation_bound(r["Q"], Wq_np) + 2.0 ** -20 * f * (Qa @ Wa.T)
+             + 2.0 ** -14 * np.abs(r["Y_r"]).max() + 1e-30)
+    assert float((np.abs(y - ref) / bound).max()) <= 1.0
+    Y0 = rtl.sparse_lora_linear_fp8(X, Wq, xs, torch.zeros_like(LA), LB, bias=b, comp=comp)
+    assert torch.equal(Y0, rtl.sparse_linear_fp8(X, Wq, xs, bias=b, comp=comp))
+
+
+@pytest.mark.parametrize("shape", [(300, 200, 384), (129, 64, 128), (520, 64, 3072), "mlp_down"])
+def test_sparse_lora_linear_fp8_operand_and_sampled_rows(shape):
+    """Ragged and full shapes: the FP8 compressed operand the one-pass sweep leaves must equal, bit for
+    bit, the one rtl_sparse_linear_fp8's sweep leaves (head of the workspace; at K = 3072 the K ranges are
+    three 64-k stages long, so range boundaries fall inside 128-k blocks), and sampled rows of Y must meet
+    the benchmark spec's bound."""
+    if isinstance(shape, str):
+        X, W = synth.workload(shape, seed=0, device=DEV)
+    else:
+        X = synth.activations("laplace_outlier", shape[0], shape[2], seed=51, device=DEV)
+        W = synth.weights(shape[1], shape[2], seed=52, device=DEV)
+    M, K = X.shape
+    N = W.shape[0]
+    LA, LB = synth.lora(N, K, 64, seed=53, device=DEV)
+    xs = fp8_scale(X)
+    Wq = rtl.quantize_fp8(W)
+    Mpad, KB = (M + 255) // 256 * 256, K // 128
+    moff = (Mpad * KB * 64 + 255) // 256 * 256
+    ws1 = torch.full((rtl.sparse_linear_fp8_workspace(M, N, K, rtl.COMP_GROUP) + 256,), 0xA5, dtype=torch.uint8, device=DEV)
+    ws2 = torch.full((rtl.sparse_lora_linear_fp8_workspace(M, N, K, 64, rtl.COMP_GROUP) + 256,), 0x5A, dtype=torch.uint8,
+                     device=DEV)
+    rtl.sparse_linear_fp8(X, Wq, xs, ws=ws1)
+    Y = rtl.sparse_lora_linear_fp8(X, Wq, xs, LA, LB, ws=ws2)
+    torch.cuda.synchronize()
+    for off, rec in ((0, 64), (moff, 16)):
+        a = ws1[off:off + Mpad * KB * rec].view(KB, Mpad, rec)[:, :M]
+        bb = ws2[off:off + Mpad * KB * rec].view(KB, Mpad, rec)[:, :M]
+        assert torch.equal(a, bb)
+    rows = sampled_rows(M, 8, seed=9)
+    sel = torch.from_numpy(rows).to(DEV)
+    r = oracle.sparse_lora_linear_fp8_oracle(synth.bits(X[sel]), Wq.cpu().numpy(), float(xs.item()), synth.bits(LA),
+                                             synth.bits(LB), scope=oracle.GROUP)
+    assert rel_max_err(y_to_np(Y[sel]), r["Y"]) <= Y_TOL
+
+
 def test_denoising_step_sweep_sampled_blocks():
     """Six of the 60 blocks of the full-step sweep, first and last included (QKV, out-proj, fc1, fc2 at
     M = 4608), fresh seeded tensors per layer: metadata in full, outputs on sampled rows."""
