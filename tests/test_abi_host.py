@@ -135,6 +135,21 @@ def test_fp8_entry_points_reject_bad_arguments():
     # half the value bytes of the bf16 workspace, same metadata
     assert L.rtl_sparse_linear_fp8_workspace(4096, 3072, 12288, 1) < L.rtl_sparse_linear_workspace(4096, 3072, 12288, 1)
 
+    def lora(X=FAKE, Wq=FAKE, xs=FAKE, LA=FAKE, LB=FAKE, Y=FAKE, M=4, N=8, K=128, R=64, ldx=128, ldw=128, ldla=64,
+             ldlb=128, ldy=8, comp=1, eps=1e-8, ws=FAKE, wsb=1 << 30):
+        return L.rtl_sparse_lora_linear_fp8(X, Wq, xs, LA, LB, None, Y, M, N, K, R, ldx, ldw, ldla, ldlb, ldy, comp,
+                                            eps, ws, wsb, None)
+
+    assert lora(R=32) == 2 and lora(ldla=32) == 2 and lora(ldlb=64) == 2 and lora(K=64, ldx=64, ldw=64, ldlb=64) == 2
+    assert lora(X=None) == 1 and lora(xs=None) == 1 and lora(LA=None) == 1 and lora(LB=None) == 1
+    assert lora(LA=FAKE + 8) == 3 and lora(ldla=68) == 3 and lora(ldw=136) == 3 and lora(xs=FAKE + 2) == 3
+    assert lora(comp=7) == 5 and lora(eps=float("nan")) == 5
+    assert lora(ws=None) == 4 and lora(wsb=64) == 4
+    assert lora(M=0) == 0 and lora(N=0) == 0
+    need = L.rtl_sparse_lora_linear_fp8_workspace(4096, 3072, 12288, 64, 1)
+    assert need > L.rtl_sparse_linear_fp8_workspace(4096, 3072, 12288, 1)       # + T planes + sweep scratch
+    assert L.rtl_sparse_lora_linear_fp8_workspace(4096, 3072, 12288, 32, 1) == 0  # rank other than 64
+
 
 def test_tile_plan_covers_the_output_exactly():
     """Host arithmetic of the launch plan: body tiles (256 x 256 or 256 x 192) on the first rows, 256 x 128

@@ -924,15 +924,17 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     xs = fp8_scale(X)
     Xs = X.clone()                                    # static input buffer of the graph
     Y1 = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
-    Y2, Y3 = torch.empty_like(Y1), torch.empty_like(Y1)
+    Y2, Y3, Y4 = torch.empty_like(Y1), torch.empty_like(Y1), torch.empty_like(Y1)
     ws1 = torch.empty(rtl.sparse_linear_workspace(M, N, K, rtl.COMP_TENSOR) + 256, dtype=torch.uint8, device=DEV)
     ws2 = torch.empty(rtl.sparse_lora_linear_workspace(M, N, K, 64) + 256, dtype=torch.uint8, device=DEV)
     ws3 = torch.empty(rtl.sparse_linear_fp8_workspace(M, N, K) + 256, dtype=torch.uint8, device=DEV)
+    ws4 = torch.empty(rtl.sparse_lora_linear_fp8_workspace(M, N, K, 64, rtl.COMP_ROW) + 256, dtype=torch.uint8, device=DEV)
 
     def run():
         rtl.sparse_linear(Xs, W, comp=rtl.COMP_TENSOR, out=Y1, ws=ws1)
         rtl.sparse_lora_linear(Xs, W, LA, LB, out=Y2, ws=ws2)
         rtl.sparse_linear_fp8(Xs, Wq, xs, out=Y3, ws=ws3)
+        rtl.sparse_lora_linear_fp8(Xs, Wq, xs, LA, LB, comp=rtl.COMP_ROW, out=Y4, ws=ws4)
 
     rtl.init()                                        # device set-up is not a stream operation: before the capture
     torch.cuda.synchronize()
@@ -942,14 +944,14 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     for seed in (5, 6, 7):
         Xn = synth.activations("laplace", M, K, seed=seed, device=DEV)
         Xs.copy_(Xn)
-        for y in (Y1, Y2, Y3):
+        for y in (Y1, Y2, Y3, Y4):
             y.zero_()
         g.replay()
         torch.cuda.synchronize()
-        got = [Y1.clone(), Y2.clone(), Y3.clone()]
+        got = [Y1.clone(), Y2.clone(), Y3.clone(), Y4.clone()]
         run()                                         # eager on the same inputs
         torch.cuda.synchronize()
-        for a, b in zip(got, (Y1, Y2, Y3)):
+        for a, b in zip(got, (Y1, Y2, Y3, Y4)):
             assert torch.equal(a, b)
         ref = oracle.sparse_linear_oracle(synth.bits(Xn), synth.bits(W), scope=oracle.TENSOR)["Y"]
         check_y(got[0], ref)
