@@ -10,6 +10,7 @@ GEMM, timed per launch with HIP events), and the CPU oracle timed on a bounded r
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -63,15 +64,20 @@ def _read_number(path):
 
 
 SMI_HELPER = r"""
-import json, subprocess, sys
+import json, re, subprocess, sys
+KEYS = ("accumulation_counter", "ppt_residency_acc", "prochot_residency_acc", "socket_thm_residency_acc",
+        "vr_thm_residency_acc", "hbm_thm_residency_acc", "current_socket_power", "current_gfxclks", "current_gfxclk")
 for line in sys.stdin:                      # one request per line; answers with one JSON line
     try:
-        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
-        card = next(iter(json.loads(out).values()))
-        sclk = next((v for k, v in card.items() if k.lower().startswith("sclk")), None)
-        print(json.dumps({"sclk": sclk}), flush=True)
+        out = subprocess.run(["rocm-smi", "--showmetrics"], capture_output=True, text=True, timeout=30).stdout
+        d = {}
+        for l in out.splitlines():
+            m = re.match(r"GPU\[0\]\s*:\s*([a-z_0-9]+)[^:]*:\s*(.*)$", l)
+            if m and m.group(1) in KEYS:
+                d[m.group(1)] = m.group(2).strip()
+        print(json.dumps(d), flush=True)
     except Exception as e:
-        print(json.dumps({"sclk": None, "error": str(e)[:80]}), flush=True)
+        print(json.dumps({"error": str(e)[:80]}), flush=True)
 """
 
 
@@ -87,14 +93,16 @@ def start_smi_helper():
         return None
 
 
-def gpu_state_under_load(step, torch, smi):
-    """Shader clock and board power WHILE `step` runs back to back. The clock comes from one `rocm-smi`
-    reading that the helper process takes while this process keeps the queue full; the power from the
-    amdgpu hwmon file (power1_average / power1_input, microwatts), polled between batches of launches
-    during the same period. Values are null when a source is not readable on the box."""
+def gpu_state_under_load(step, torch, smi, seconds=3.0):
+    """What the power management does WHILE `step` runs back to back, from the firmware's own metrics table
+    (`rocm-smi --showmetrics`, run by the helper process): socket power and the shader clocks of the 8 XCDs
+    from a reading taken mid-run, and the share of the firmware's samples during which each throttler was
+    active (residency accumulators, read right before and right after the load). Next to it the amdgpu hwmon
+    power file, polled between batches of launches. Values are null when a source is not readable."""
     import glob
     import select
-    out = {"sclk_mhz": None, "power_w": None, "power_cap_w": None, "source": None}
+    out = {"sclk_mhz": None, "socket_power_w": None, "throttler_residency": None, "power_w": None, "power_cap_w": None,
+           "source": None}
     cap = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
     if cap and _read_number(cap[0]) is not None:
         out["power_cap_w"] = round(_read_number(cap[0]) / 1e6, 0)
@@ -104,40 +112,78 @@ def gpu_state_under_load(step, torch, smi):
         if hits and _read_number(hits[0]) is not None:
             pw = hits[0]
             break
-    p_s = []
-    answer = None
-    if smi is not None and smi.poll() is None:
+
+    def ask():
+        nonlocal smi
+        if smi is None or smi.poll() is not None:
+            return False
         try:
             smi.stdin.write("read\n")
             smi.stdin.flush()
+            return True
         except Exception:
             smi = None
-    t_end = time.perf_counter() + (20.0 if smi is not None else 0.25)
-    while time.perf_counter() < t_end:
+            return False
+
+    def answer(block_s):
+        if smi is None or not select.select([smi.stdout], [], [], block_s)[0]:
+            return None
+        try:
+            return json.loads(smi.stdout.readline())
+        except Exception:
+            return None
+
+    torch.cuda.synchronize()
+    before = answer(30.0) if ask() else None           # idle reading right before the load
+    p_s = []
+    mid = None
+    asked = False
+    t0 = time.perf_counter()
+    t_end = t0 + (seconds if smi is not None else 0.25)
+    while time.perf_counter() < t_end or (asked and mid is None and time.perf_counter() < t0 + 30.0):
         for _ in range(8):
             step()
         torch.cuda.synchronize()
         if pw:
             p_s.append(_read_number(pw))
-        if smi is not None and select.select([smi.stdout], [], [], 0)[0]:
-            answer = smi.stdout.readline()
-            break
+        if not asked and time.perf_counter() > t0 + 1.0:   # the chip has been under this load for a second
+            asked = ask()
+            if not asked:
+                break
+        if asked and mid is None:
+            mid = answer(0)
     torch.cuda.synchronize()
+    after = answer(30.0) if ask() else None
     sources = []
-    if answer:
+    if mid:
         try:
-            sclk = json.loads(answer).get("sclk")
-            digits = "".join(ch for ch in str(sclk) if ch.isdigit() or ch == ".")
-            if sclk is not None and digits:
-                out["sclk_mhz"] = float(digits)
-                sources.append("sclk: rocm-smi --showclocks (run by a helper process), read while the step runs back to back")
+            clk = [float(v) for v in re.findall(r"[0-9.]+", mid.get("current_gfxclks", "") or mid.get("current_gfxclk", ""))]
+            if clk:
+                out["sclk_mhz"] = {"mean": round(sum(clk) / len(clk), 0), "min": min(clk), "max": max(clk)}
+            if mid.get("current_socket_power", "").replace(".", "").isdigit():
+                out["socket_power_w"] = float(mid["current_socket_power"])
+            sources.append("sclk (per XCD) and socket power: rocm-smi --showmetrics (run by a helper process), one reading "
+                           "taken while the step runs back to back")
+        except Exception:
+            pass
+    if before and after:
+        try:
+            n = int(after["accumulation_counter"]) - int(before["accumulation_counter"])
+            res = {"samples": n}
+            for k in ("ppt", "prochot", "socket_thm", "vr_thm", "hbm_thm"):
+                res[k] = round((int(after[k + "_residency_acc"]) - int(before[k + "_residency_acc"])) / max(n, 1), 3)
+            res["note"] = ("share of the firmware's samples between a reading right before and one right after the load "
+                           "during which the throttler was active (ppt = package power limit); the window also holds the "
+                           "idle time the two readings themselves take")
+            out["throttler_residency"] = res
+            sources.append("throttlers: residency accumulators of the same table")
         except Exception:
             pass
     p_s = [v for v in p_s if v]
     if p_s:
         out["power_w"] = {"mean": round(sum(p_s) / len(p_s) / 1e6, 0), "max": round(max(p_s) / 1e6, 0),
                           "samples": len(p_s)}
-        sources.append("power: amdgpu hwmon %s, polled during the same period" % os.path.basename(pw))
+        sources.append("power_w: amdgpu hwmon %s, polled during the same period" % os.path.basename(pw))
     out["source"] = "; ".join(sources) or None
     return out
 
@@ -328,6 +374,13 @@ def main():
     ap.add_argument("--only-core", action="store_true",
                     help="time only the step, its pack kernel and the two dense GEMMs (no LoRA, FP8, cold-cache, "
                          "peak-probe or clock legs): the short command the rocprofv3 summaries under profiles/ use")
+    ap.add_argument("--sustain", default=None,
+                    choices=["sparse_linear", "sparse_linear_zero_operands", "dense_linear", "hipblaslt_dense", "pack",
+                             "smfmac_random", "smfmac_constant"],
+                    help="run ONE kind of call back to back for --seconds and print what the power management did "
+                         "meanwhile (clocks, socket power, throttler residency from the firmware's metrics table); "
+                         "no metric line")
+    ap.add_argument("--seconds", type=float, default=6.0, help="with --sustain: length of the load")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (3 launches): reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -372,6 +425,42 @@ def main():
 
     def step():
         rtl.sparse_linear(X, W, comp=comp, out=Y, ws=ws)
+
+    if args.sustain:
+        kind = args.sustain
+        if kind == "sparse_linear_zero_operands":     # same launches, no switching activity in the data paths
+            X.zero_()
+            W.zero_()
+        ops = None
+        if kind.startswith("smfmac"):
+            ops = (torch.randn(64 * 24, device=dev) if kind == "smfmac_random" else torch.ones(64 * 24, device=dev)).to(torch.bfloat16)
+        load = {"sparse_linear": step, "sparse_linear_zero_operands": step,
+                "dense_linear": lambda: rtl.dense_linear(X, W, out=Y, ws=wsd),
+                "hipblaslt_dense": lambda: torch.matmul(X, W.t(), out=Y),
+                "pack": lambda: rtl.diag_pack_sweep(X, comp, ws=ws),
+                "smfmac_random": lambda: rtl.diag_matrix_rate(1, ops, 4000, 1024),
+                "smfmac_constant": lambda: rtl.diag_matrix_rate(1, ops, 4000, 1024)}[kind]
+        for _ in range(20):
+            load()
+        torch.cuda.synchronize()
+        n, t0 = 0, time.perf_counter()
+
+        def counted():
+            nonlocal n
+            n += 1
+            load()
+
+        state = gpu_state_under_load(counted, torch, smi, seconds=args.seconds)
+        print(json.dumps({"sustain": kind, "workload": args.workload, "calls": n,
+                          "note": "wall time per call is not reported here: the loop also waits for the helper's readings",
+                          "gpu_state_under_load": state}))
+        if smi is not None:
+            try:
+                smi.stdin.close()
+                smi.wait(timeout=5)
+            except Exception:
+                pass
+        return
 
     # ---- spin-up (untimed): a fresh process finds the chip at idle clocks; everything below, the
     #      context legs and the timed region alike, is measured at the working point
