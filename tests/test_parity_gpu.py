@@ -1058,7 +1058,7 @@ def test_randomized_pack_cases_bit_exact():
 
 def test_randomized_linear_cases():
     """Seeded sweep over M, N (any), K (multiples of 128), scopes, bias on/off for the sparse, dense,
-    LoRA and FP8 linears against the oracle."""
+    LoRA, FP8 and FP8 + LoRA linears against the oracle."""
     rng = np.random.default_rng(2025)
     kinds = ["laplace", "gelu", "normal", "laplace_outlier"]
     for _ in range(24):
@@ -1082,3 +1082,7 @@ def test_randomized_linear_cases():
         elif comp == rtl.COMP_TENSOR:
             f = f * r8["s"][0]
         check_y_fp8(rtl.sparse_linear_fp8(X, Wq, xs, bias=bias, comp=comp), r8, Wq.cpu().numpy(), f, bias=bb)
+        r8l = oracle.sparse_lora_linear_fp8_oracle(Xb, Wq.cpu().numpy(), float(xs.item()), synth.bits(LA), synth.bits(LB),
+                                                   bias=bb, scope=comp)
+        y8l = y_to_np(rtl.sparse_lora_linear_fp8(X, Wq, xs, LA, LB, bias=bias, comp=comp))
+        assert rel_max_err(y8l, r8l["Y"]) <= Y_TOL
