@@ -188,6 +188,49 @@ def gpu_state_under_load(step, torch, smi, seconds=3.0):
     return out
 
 
+def energy_per_call(calls, torch, seconds=2.5):
+    """Joules per call of each callable in `calls` (name -> function): the call runs back to back for
+    `seconds`; the amdgpu hwmon power file (a moving average of the socket power) is polled between batches
+    of launches, and the mean of the readings of the last second is multiplied by the time per call over
+    that same second. None where the file is not readable."""
+    import glob
+    pw = None
+    for name in ("power1_average", "power1_input"):
+        hits = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/" + name))
+        if hits and _read_number(hits[0]) is not None:
+            pw = hits[0]
+            break
+    if pw is None:
+        return None
+    out = {}
+    for name, fn in calls.items():
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        marks = []                                   # (time, calls so far, power reading)
+        n = 0
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(64):
+                fn()
+            n += 64
+            torch.cuda.synchronize()
+            marks.append((time.perf_counter() - t0, n, _read_number(pw)))
+        tail = [m for m in marks if m[0] >= seconds - 1.0 and m[2]]
+        if len(tail) < 2:
+            out[name] = None
+            continue
+        watts = sum(m[2] for m in tail) / len(tail) / 1e6
+        us = (tail[-1][0] - tail[0][0]) / (tail[-1][1] - tail[0][1]) * 1e6
+        out[name] = {"socket_w": round(watts, 0), "us_per_call_wall": round(us, 1), "joules_per_call": round(watts * us * 1e-6, 4)}
+    a, b = out.get("sparse_linear"), out.get("dense_linear")
+    if a and b:
+        out["dense_over_sparse"] = round(b["joules_per_call"] / a["joules_per_call"], 3)
+    out["how"] = ("each call back to back for %.1f s; socket power = mean of the amdgpu hwmon readings (%s) of the last "
+                  "second, time per call = wall clock over the same second" % (seconds, os.path.basename(pw)))
+    return out
+
+
 def matrix_rate_probe(rtl, torch, dev, kind, random_operands):
     """Measured ceiling of the matrix instruction (rtl_diag_matrix_rate): executed TFLOP/s from HIP
     events, shader clock from the kernel's own cycle counter against the 100 MHz counter."""
@@ -577,6 +620,8 @@ def main():
                            "mall_resident": context_leg("fill mall", lambda: fill_rate_probe(rtl, torch, dev, 96))},
     }
     gpu_state = None if args.only_core else context_leg("gpu state", lambda: gpu_state_under_load(step, torch, smi))
+    energy = None if args.only_core else context_leg("energy", lambda: energy_per_call(
+        {"sparse_linear": step, "dense_linear": lambda: rtl.dense_linear(X, W, out=Y, ws=wsd)}, torch))
     if smi is not None:
         try:
             smi.stdin.close()
@@ -687,6 +732,7 @@ def main():
         "timing": timing,
         "measured_peaks": peaks,
         "gpu_state_under_load": gpu_state,
+        "energy_per_call": energy,
         "paper_context": "paper reports 1.88x kernel / 1.55x linear-layer speedup on NVIDIA H20 (other hardware)",
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
